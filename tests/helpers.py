@@ -1,0 +1,129 @@
+"""Hand-built scenes and small utilities shared by the tests (no step arithmetic here)."""
+import numpy as np
+
+import scenegen
+
+
+def params(**kw):
+    p = scenegen.default_params(kw.pop("n_substeps", 1), kw.pop("n_iters", 5), kw.pop("dt", 1.0 / 60.0))
+    p.update(kw)
+    return p
+
+
+class SceneBuilder:
+    """One environment at a time; polygons occupy shape indices 0..P-1, circles P..P+C-1."""
+
+    def __init__(self, caps, n_envs=1):
+        self.caps = caps
+        self.P, self.C, self.J, self.T = caps
+        self.sc = scenegen.empty_scene(caps, n_envs)
+        self.n_poly = [0] * n_envs
+        self.n_circ = [0] * n_envs
+        self.n_joint = [0] * n_envs
+        self.n_thr = [0] * n_envs
+
+    def _body(self, e, i, pos, theta, vel, omega, inv_m, inv_i, friction, restitution, density, role):
+        s = self.sc
+        s["pos"][e, i] = pos
+        s["theta"][e, i] = theta
+        s["vel"][e, i] = vel
+        s["omega"][e, i] = omega
+        s["inv_mass"][e, i] = inv_m
+        s["inv_inertia"][e, i] = inv_i
+        s["friction"][e, i] = friction
+        s["restitution"][e, i] = restitution
+        s["density"][e, i] = density
+        s["role"][e, i] = role
+        s["active"][e, i] = 1
+
+    def polygon(self, verts, pos, theta=0.0, vel=(0, 0), omega=0.0, density=1.0, static=False, friction=0.5,
+                restitution=0.0, role=0, e=0):
+        i = self.n_poly[e]
+        assert i < self.P
+        self.n_poly[e] += 1
+        v = np.zeros((4, 2))
+        n = len(verts)
+        v[:n] = verts
+        v2, im, ii = scenegen.polygon_mass_props(v[None], np.array([n]), np.array([density]))
+        # the caller's frame must already be centred on the centroid
+        assert np.allclose(v2[0, :n], v[:n], atol=1e-12), "polygon vertices must be centred on the centroid"
+        self.sc["verts"][e, i] = v
+        self.sc["n_verts"][e, i] = n
+        if static:
+            im, ii = np.zeros(1), np.zeros(1)
+        self._body(e, i, pos, theta, vel, omega, im[0], ii[0], friction, restitution, density, role)
+        return i
+
+    def box(self, hx, hy, pos, **kw):
+        return self.polygon(scenegen.box_verts(hx, hy), pos, **kw)
+
+    def circle(self, r, pos, theta=0.0, vel=(0, 0), omega=0.0, density=1.0, static=False, friction=0.5,
+               restitution=0.0, role=0, e=0):
+        k = self.n_circ[e]
+        assert k < self.C
+        self.n_circ[e] += 1
+        i = self.P + k
+        im, ii = scenegen.circle_mass_props(np.array([r]), np.array([density]))
+        if static:
+            im, ii = np.zeros(1), np.zeros(1)
+        self.sc["radius"][e, k] = r
+        self._body(e, i, pos, theta, vel, omega, im[0], ii[0], friction, restitution, density, role)
+        return i
+
+    def joint(self, a, b, world_anchor, fixed=False, motor_on=False, speed=0.0, power=0.0, e=0):
+        q = self.n_joint[e]
+        assert q < self.J
+        self.n_joint[e] += 1
+        s = self.sc
+        wa = np.asarray(world_anchor, dtype=np.float64)
+
+        def local(i):
+            d = wa - s["pos"][e, i]
+            c, sn = np.cos(-s["theta"][e, i]), np.sin(-s["theta"][e, i])
+            return np.array([c * d[0] - sn * d[1], sn * d[0] + c * d[1]])
+
+        s["joint_active"][e, q] = 1
+        s["joint_a"][e, q], s["joint_b"][e, q] = a, b
+        s["joint_anchor_a"][e, q] = local(a)
+        s["joint_anchor_b"][e, q] = local(b)
+        s["joint_fixed"][e, q] = int(fixed)
+        s["joint_theta_f"][e, q] = s["theta"][e, a] - s["theta"][e, b]
+        s["joint_motor_on"][e, q] = int(motor_on)
+        s["joint_motor_speed"][e, q] = speed
+        s["joint_motor_power"][e, q] = power
+        return q
+
+    def thruster(self, body, local_pos, angle, power, e=0):
+        k = self.n_thr[e]
+        assert k < self.T
+        self.n_thr[e] += 1
+        s = self.sc
+        s["thruster_active"][e, k] = 1
+        s["thruster_body"][e, k] = body
+        s["thruster_pos"][e, k] = local_pos
+        s["thruster_angle"][e, k] = angle
+        s["thruster_power"][e, k] = power
+        return k
+
+    def scene(self, f32=True):
+        return scenegen.to_f32(self.sc) if f32 else {k: v.copy() for k, v in self.sc.items()}
+
+
+def pair_index(i, j, N):
+    return i * (2 * N - i - 1) // 2 + (j - i - 1)
+
+
+def zeros_actions(n_steps, n_envs, caps):
+    return np.zeros((n_steps, n_envs, caps[2] + caps[3]))
+
+
+def energy(sc, state, g):
+    """Kinetic + potential energy of the dynamic bodies."""
+    im, ii = sc["inv_mass"], sc["inv_inertia"]
+    dyn = (im > 0) & (sc["active"] > 0)
+    m = np.where(dyn, 1.0 / np.where(im > 0, im, 1.0), 0.0)
+    I = np.where(dyn & (ii > 0), 1.0 / np.where(ii > 0, ii, 1.0), 0.0)
+    v2 = (state["vel"].reshape(im.shape + (2,)) ** 2).sum(-1)
+    ke = 0.5 * m * v2 + 0.5 * I * state["omega"] ** 2
+    pe = m * (-g) * state["pos"].reshape(im.shape + (2,))[..., 1]
+    return (ke + pe).sum(-1)
