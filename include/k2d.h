@@ -1,0 +1,142 @@
+/* k2d.h -- C boundary of the MI355X-native batched 2D rigid-body step.
+ *
+ * The library steps thousands of independent scenes ("environments") of the paper's physics engine
+ * (Sec. 3.1; Appendix A, Algorithm 1): every scene is a set of fixed-capacity arrays of convex polygons,
+ * circles, joints and thrusters with active masks (capacities per environment class: Table 4).
+ *
+ * Conventions
+ *   - every function returns 0 (K2D_OK) or a negative K2D_E_* code; nothing throws, exits or prints;
+ *   - pointers named *_dev are DEVICE pointers owned by the caller (e.g. torch tensors); the library never
+ *     allocates or frees device memory; `k2d_batch` is a small HOST descriptor owned by the library;
+ *   - all device work is enqueued on the caller's stream (`void* stream` is a hipStream_t, NULL = the null
+ *     stream) and no call synchronises with the host;
+ *   - calls on the same batch must be ordered by the caller (same stream, or events between streams).
+ */
+#ifndef K2D_H_
+#define K2D_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define K2D_OK 0
+#define K2D_E_ARG (-1)   /* NULL pointer, non-positive count, misaligned buffer          */
+#define K2D_E_CAP (-2)   /* capacities not one of the supported classes (Table 4 sizes) */
+#define K2D_E_SIZE (-3)  /* buffer too small, n_envs does not match the batch          */
+#define K2D_E_HIP (-4)   /* a HIP call or kernel launch failed                          */
+
+/* Capacities of one environment (Table 4): polygons, circles, joints, thrusters.
+ * Supported: {5,2,1,1} (Small), {6,3,2,2} (Medium), {12,4,6,2} (Large).
+ * Shapes share one index space: polygons 0..P-1, then circles P..P+C-1. */
+typedef struct {
+  int32_t n_polygons, n_circles, n_joints, n_thrusters;
+} k2d_caps;
+
+/* Parameters of the step, fixed when the batch is created.  The paper names the coefficients but prints no
+ * values (A.3.7: alpha, beta; A.4.2: gamma; A.5: rho; Algorithm 1: num_solver_steps, warm starting). */
+typedef struct {
+  float dt;                    /* time of one step; a substep lasts dt / n_substeps                    */
+  float gravity_y;             /* added to v.y of every active dynamic shape, times the substep        */
+  int32_t n_substeps;          /* passes of the body of Algorithm 1 per step (same action for all)     */
+  int32_t n_iters;             /* num_solver_steps of Algorithm 1                                      */
+  int32_t warm_start;          /* A.7: start from last substep's accumulated impulses                  */
+  float alpha;                 /* A.3.7 velocity correction: bias speed = alpha * max(pen - slop, 0)   */
+  float beta;                  /* A.3.7 positional correction: move apart by beta * max(pen - slop, 0) */
+  float gamma;                 /* A.4.2 fixed-joint angular correction speed per radian of error       */
+  float rho;                   /* A.5 motor: impulse = power * tanh((w_a - w_b - speed*A) * rho) * dt  */
+  float slop;                  /* penetration left uncorrected (0 = literal A.3.7)                     */
+  float restitution_threshold; /* approach speeds at or below it take e = 0 (resting contact)          */
+  int32_t clip_thruster_01;    /* clamp thruster actions to [0,1] (Sec. 3.2 continuous action range)   */
+  float joint_alpha;           /* A.4.1 velocity correction of the joint point constraint, 1/s         */
+  float joint_beta;            /* A.4.1 positional correction of the joint point constraint            */
+  float tie_eps;               /* A.3.4: b's face is the reference face only if it wins by tie_eps     */
+} k2d_params;
+
+/* Word (4-byte) offsets inside one environment record.  A record is an array of 32-bit words, floats
+ * unless marked (i) = int32.  Arrays are stored component-major ("structure of arrays" inside the
+ * environment): entry i of array X is word X + i.  The first `scene_words` words are the scene
+ * description (what k2d_reset consumes); the full `state_words` record adds the contact accumulators.
+ *
+ *   per shape (N = P + C entries each):
+ *     pos_x pos_y theta vel_x vel_y omega inv_mass inv_inertia friction restitution density
+ *     shape_flags(i): bit0 = active, bits 8.. = role (passed through to the observation)
+ *   per polygon (P entries each):  n_verts(i) in {3,4};  verts: 8 arrays [P], array 2*v+c holds
+ *     coordinate c of local vertex v (counter-clockwise, centred on the centre of mass)
+ *   per circle (C): radius
+ *   per joint (J): joint_flags(i): bit0 active, bit1 fixed, bit2 motor on;  joint_a(i) joint_b(i) shape indices;
+ *     anchor_a_x anchor_a_y anchor_b_x anchor_b_y (local frames); theta_f; motor_speed; motor_power;
+ *     acc_x acc_y (accumulated point impulse, A.7); acc_ang (accumulated angular impulse of a fixed joint)
+ *   per thruster (T): thr_flags(i): bit0 active; thr_body(i); pos_x pos_y (local); angle; power
+ *   -- end of scene description --
+ *   lambda: [n_pairs][4] = accumulated (normal, friction) impulse of manifold point 0 and of point 1 (A.7);
+ *     pairs in lexicographic order of (i < j): index = i*(2N-i-1)/2 + (j-i-1)
+ *   pair_state: n_pairs BYTES (padded to a word): bit k = manifold point k was an active collision at the
+ *     last substep (Table 2: penetration > 0)
+ */
+typedef struct {
+  int32_t n_shapes, n_pairs;
+  int32_t pos_x, pos_y, theta, vel_x, vel_y, omega, inv_mass, inv_inertia, friction, restitution, density,
+      shape_flags;
+  int32_t n_verts, verts, radius;
+  int32_t joint_flags, joint_a, joint_b, anchor_a_x, anchor_a_y, anchor_b_x, anchor_b_y, theta_f, motor_speed,
+      motor_power, acc_x, acc_y, acc_ang;
+  int32_t thr_flags, thr_body, thr_pos_x, thr_pos_y, thr_angle, thr_power;
+  int32_t scene_words;
+  int32_t lambda, pair_state;
+  int32_t state_words;   /* words of one record as exchanged through k2d_read_state / k2d_write_state */
+  int32_t obs_dim;       /* floats per environment written by k2d_read_obs                            */
+} k2d_layout;
+
+typedef struct k2d_batch k2d_batch; /* opaque host descriptor */
+
+/* Fills `out` for the given capacities.  K2D_E_CAP if unsupported. */
+int k2d_get_layout(const k2d_caps* caps, k2d_layout* out);
+
+/* Bytes of device memory the caller must provide for `n_envs` environments (0 on bad arguments). */
+size_t k2d_state_bytes(const k2d_caps* caps, int n_envs);
+
+/* Binds a caller-owned device buffer (>= k2d_state_bytes, 256-byte aligned) as the state of a new batch.
+ * The buffer's contents are undefined until k2d_reset or k2d_write_state has covered every environment. */
+int k2d_alloc_batch(const k2d_caps* caps, const k2d_params* params, int n_envs, void* state_dev,
+                    size_t state_bytes, k2d_batch** out);
+
+/* Frees the host descriptor only. */
+int k2d_free_batch(k2d_batch* batch);
+
+/* Starts new episodes: scenes_dev holds n records of `scene_words` words (layout above), record r goes to
+ * environment env_ids_dev[r] (NULL: environment r).  Joint and contact accumulators and the pair states
+ * of those environments are zeroed.  Indices out of range are skipped. */
+int k2d_reset(k2d_batch* batch, const void* scenes_dev, const int32_t* env_ids_dev, int n, void* stream);
+
+/* Advances every environment by n_steps steps of the engine's main loop (Algorithm 1: gravity, collision
+ * manifolds of all shape pairs (A.3.1-A.3.4), motors (A.5), thrusters (A.6), warm starting (A.7), n_iters
+ * sweeps of joint (A.4) then collision (A.3.5-A.3.7) constraints, Euler step, positional corrections),
+ * each step being n_substeps passes with the same action.
+ * actions_dev: float [n_steps][n_envs][J+T]: first the J motor actions, then the T thruster actions.
+ * n_envs must equal the batch's. */
+int k2d_step(k2d_batch* batch, const float* actions_dev, int n_envs, int n_steps, void* stream);
+
+/* Flat symbolic observation (the physical entries of Tables 5-7), float [n_envs][obs_dim]; per polygon:
+ * pos 2, vel 2, inv_mass, inv_inertia, density, tanh(omega/10), sin theta, cos theta, friction, restitution,
+ * vertices 8, n_verts, active, role (23); per circle the same 12 then radius, active, role (15); per joint:
+ * active, fixed, anchor_a 2, anchor_b 2, motor power, motor speed, motor on, sin/cos(theta_a - theta_b) (11);
+ * per thruster: active, pos 2, power, sin/cos(angle) (6). */
+int k2d_read_obs(k2d_batch* batch, float* obs_dev, void* stream);
+
+/* Collisions of the last substep: pair_count_dev uint8 [n_envs][n_pairs] = active manifold points of the
+ * pair (0, 1 or 2; lexicographic pair order); shape_adj_dev uint32 [n_envs][N]: bit j of word i set iff
+ * shapes i and j are in active collision.  Either pointer may be NULL. */
+int k2d_read_contacts(k2d_batch* batch, uint8_t* pair_count_dev, uint32_t* shape_adj_dev, void* stream);
+
+/* Copies full records ([n_envs][state_words] words, layout above) out of / into the batch
+ * (checkpoint and resume; k2d_write_state keeps the accumulators it is given). */
+int k2d_read_state(k2d_batch* batch, void* records_dev, void* stream);
+int k2d_write_state(k2d_batch* batch, const void* records_dev, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* K2D_H_ */

@@ -72,6 +72,66 @@ template <class R> inline V2<R> cross(R w, V2<R> r) { return {-w * r.y, w * r.x}
 template <class R> inline V2<R> rotate(R c, R s, V2<R> l) { return {c * l.x - s * l.y, s * l.x + c * l.y}; }
 
 // ----------------------------------------------------------------------------------------------
+// sin, cos and tanh.  In double they are libm's.  In fp32 -- the engine's precision -- they are fixed
+// sequences of IEEE fp32 operations (round-to-nearest, no fused multiply-add), so that every
+// implementation of the engine that performs the same sequence gets the same bits whatever maths
+// library it links: quadrant reduction with a three-term split of pi/2 followed by polynomials in r^2
+// for sin and cos; tanh from a polynomial below 0.55 and from 1 - 2/(e^{2|x|} + 1) above, e^t by
+// reduction with a two-term split of ln 2 and a polynomial.  The coefficients are least-squares fits
+// on Chebyshev nodes.  Pinned against libm in double: |error| < 1.5e-7 (tests/test_oracle_math.py).
+// ----------------------------------------------------------------------------------------------
+template <class R>
+struct Fn {
+  static void sincos(R x, R& s, R& c) { s = std::sin(x); c = std::cos(x); }
+  static R tanh(R x) { return std::tanh(x); }
+};
+template <>
+struct Fn<float> {
+  static void sincos(float x, float& sn, float& cs) {
+    const float k = std::nearbyint(x * 0x1.45f306p-1f);                       // x * 2/pi, to nearest even
+    float r = x - k * 0x1.92p+0f;                                             // pi/2 = 1.5703125
+    r = r - k * 0x1.fb4p-12f;                                                 //      + 4.8375130e-4
+    r = r - k * 0x1.4442d2p-24f;                                              //      + 7.5497901e-8
+    const float z = r * r;
+    const float ps = (-0x1.9b021cp-13f * z + 0x1.110ccap-7f) * z + -0x1.555554p-3f;
+    const float pc = (0x1.9c05c8p-16f * z + -0x1.6c1354p-10f) * z + 0x1.555554p-5f;
+    const float s = r + (r * z) * ps;
+    const float c = (1.0f - 0.5f * z) + (z * z) * pc;
+    switch (static_cast<int>(k) & 3) {
+      case 0: sn = s; cs = c; break;
+      case 1: sn = c; cs = -s; break;
+      case 2: sn = -s; cs = -c; break;
+      default: sn = -c; cs = s; break;
+    }
+  }
+  static float tanh(float x) {
+    const float a = std::fabs(x);
+    float y;
+    if (a < 0.55f) {
+      const float z = a * a;
+      const float p = (((-0x1.b3b502p-8f * z + 0x1.5d873cp-6f) * z + -0x1.b9aa82p-5f) * z + 0x1.111018p-3f) * z +
+                      -0x1.555554p-2f;
+      y = a + (a * z) * p;
+    } else {
+      const float t2 = 2.0f * a;
+      const float t = (t2 < 40.0f) ? t2 : 40.0f;
+      const float n = std::nearbyint(t * 0x1.715476p+0f);                      // t * log2(e)
+      float r = t - n * 0x1.62cp-1f;                                           // ln 2 = 0.69287109375
+      r = r - n * 0x1.217f7ep-12f;                                             //      + 2.7608682e-4
+      const float p = (((0x1.6d435ap-10f * r + 0x1.120b66p-7f) * r + 0x1.5554e8p-5f) * r + 0x1.5554dcp-3f) * r + 0.5f;
+      float e = (1.0f + r) + (r * r) * p;
+      e = std::ldexp(e, static_cast<int>(n));
+      y = 1.0f - 2.0f / (e + 1.0f);
+    }
+    return x < 0.0f ? -y : y;
+  }
+};
+
+// (cos, sin) of an angle, and a vector turned by an angle
+template <class R> inline V2<R> unit(R angle) { R s, c; Fn<R>::sincos(angle, s, c); return {c, s}; }
+template <class R> inline V2<R> turn(R angle, V2<R> l) { V2<R> u = unit(angle); return rotate(u.x, u.y, l); }
+
+// ----------------------------------------------------------------------------------------------
 // Scene: fixed-capacity arrays with active masks (Sec. 3.1; capacities of Table 4).
 // Shapes share one index space: polygons 0..P-1, circles P..P+C-1.  Body position = centre of mass.
 // ----------------------------------------------------------------------------------------------
@@ -180,7 +240,8 @@ template <class R>
 WorldPoly<R> world_polygon(const Body<R>& b) {
   WorldPoly<R> wp;
   wp.n = b.n_verts;
-  R c = std::cos(b.theta), s = std::sin(b.theta);
+  R c, s;
+  Fn<R>::sincos(b.theta, s, c);
   for (int i = 0; i < wp.n; ++i) wp.w[i] = b.pos + rotate(c, s, b.verts[i]);
   for (int i = 0; i < wp.n; ++i) {
     V2<R> e = wp.w[(i + 1) % wp.n] - wp.w[i];
@@ -344,6 +405,7 @@ struct JointRow {   // fixed for one substep
   int live = 0;
   V2<R> ra, rb;
   R k11 = 0, k12 = 0, k22 = 0;   // 2x2 effective-mass matrix of the point constraint
+  R inv_det = 0;                 // 1 / its determinant
   V2<R> bias{0, 0};
   R ang_mass = 0, ang_bias = 0;
 };
@@ -402,8 +464,7 @@ void solve_joint(Env<R>& E, Joint<R>& jt, const JointRow<R>& jr) {
   // separation" is singular at zero separation and cannot remove tangential relative velocity).
   V2<R> cdot = rel_vel(a, jr.ra, b, jr.rb);
   V2<R> rhs{-(cdot.x + jr.bias.x), -(cdot.y + jr.bias.y)};
-  R det = jr.k11 * jr.k22 - jr.k12 * jr.k12;
-  V2<R> j{(jr.k22 * rhs.x - jr.k12 * rhs.y) / det, (jr.k11 * rhs.y - jr.k12 * rhs.x) / det};
+  V2<R> j{(jr.k22 * rhs.x - jr.k12 * rhs.y) * jr.inv_det, (jr.k11 * rhs.y - jr.k12 * rhs.x) * jr.inv_det};
   apply_impulse(a, j, jr.ra);
   apply_impulse(b, V2<R>{-j.x, -j.y}, jr.rb);
   jt.acc = jt.acc + j;
@@ -496,12 +557,13 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
     if (!P.warm_start) { jt.acc = {0, 0}; jt.acc_ang = 0; }
     const Body<R>& a = E.bodies[jt.a];
     const Body<R>& b = E.bodies[jt.b];
-    jr.ra = rotate(std::cos(a.theta), std::sin(a.theta), jt.anchor_a);
-    jr.rb = rotate(std::cos(b.theta), std::sin(b.theta), jt.anchor_b);
+    jr.ra = turn(a.theta, jt.anchor_a);
+    jr.rb = turn(b.theta, jt.anchor_b);
     R ms = a.inv_mass + b.inv_mass;
     jr.k11 = ms + a.inv_inertia * jr.ra.y * jr.ra.y + b.inv_inertia * jr.rb.y * jr.rb.y;
     jr.k22 = ms + a.inv_inertia * jr.ra.x * jr.ra.x + b.inv_inertia * jr.rb.x * jr.rb.x;
     jr.k12 = -a.inv_inertia * jr.ra.x * jr.ra.y - b.inv_inertia * jr.rb.x * jr.rb.y;
+    jr.inv_det = R(1) / (jr.k11 * jr.k22 - jr.k12 * jr.k12);
     V2<R> sep = (a.pos + jr.ra) - (b.pos + jr.rb);
     jr.bias = R(P.joint_alpha) * sep;
     R is = a.inv_inertia + b.inv_inertia;
@@ -519,7 +581,7 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
     if (!jrs[q].live || jt.fixed || !jt.motor_on) continue;
     R A = R(actions[q]);
     R arg = (E.bodies[jt.a].omega - E.bodies[jt.b].omega - jt.motor_speed * A) * R(P.rho);
-    motor[q] = jt.motor_power * std::tanh(arg) * h;
+    motor[q] = jt.motor_power * Fn<R>::tanh(arg) * h;
   }
   for (int q = 0; q < nJ; ++q) {
     if (motor[q] == R(0)) continue;
@@ -537,9 +599,9 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
     if (!b.active) continue;
     R A = R(actions[nJ + q]);
     if (P.clip_thruster_01) A = std::min(std::max(A, R(0)), R(1));
-    R c = std::cos(b.theta), s = std::sin(b.theta);
-    V2<R> dir = rotate(c, s, V2<R>{std::cos(th.angle), std::sin(th.angle)});
-    V2<R> r = rotate(c, s, th.pos);
+    V2<R> u = unit(b.theta);
+    V2<R> dir = rotate(u.x, u.y, unit(th.angle));
+    V2<R> r = rotate(u.x, u.y, th.pos);
     V2<R> imp = (th.power * A * h) * dir;
     apply_impulse(b, imp, r);
   }
@@ -636,8 +698,8 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
     const Joint<R>& jt = E.joints[q];
     Body<R>& a = E.bodies[jt.a];
     Body<R>& b = E.bodies[jt.b];
-    V2<R> xa = a.pos + rotate(std::cos(a.theta), std::sin(a.theta), jt.anchor_a);
-    V2<R> xb = b.pos + rotate(std::cos(b.theta), std::sin(b.theta), jt.anchor_b);
+    V2<R> xa = a.pos + turn(a.theta, jt.anchor_a);
+    V2<R> xb = b.pos + turn(b.theta, jt.anchor_b);
     V2<R> c = (R(P.joint_beta) / (a.inv_mass + b.inv_mass)) * (xa - xb);
     a.pos = a.pos - a.inv_mass * c;
     b.pos = b.pos + b.inv_mass * c;
@@ -822,8 +884,8 @@ struct Batch : BatchBase {
         const Body<R>& b = E.bodies[i];
         *o++ = b.pos.x; *o++ = b.pos.y; *o++ = b.vel.x; *o++ = b.vel.y;
         *o++ = b.inv_mass; *o++ = b.inv_inertia; *o++ = b.density;
-        *o++ = std::tanh(b.omega / R(10));
-        *o++ = std::sin(b.theta); *o++ = std::cos(b.theta);
+        *o++ = Fn<R>::tanh(b.omega / R(10));
+        { V2<R> u = unit(b.theta); *o++ = u.y; *o++ = u.x; }
         *o++ = b.friction; *o++ = b.restitution;
         if (i < P) {
           for (int k = 0; k < 4; ++k) { *o++ = b.verts[k].x; *o++ = b.verts[k].y; }
@@ -838,11 +900,11 @@ struct Batch : BatchBase {
         *o++ = j.active; *o++ = j.fixed;
         *o++ = j.anchor_a.x; *o++ = j.anchor_a.y; *o++ = j.anchor_b.x; *o++ = j.anchor_b.y;
         *o++ = j.motor_power; *o++ = j.motor_speed; *o++ = j.motor_on;
-        *o++ = std::sin(rel); *o++ = std::cos(rel);
+        { V2<R> u = unit(rel); *o++ = u.y; *o++ = u.x; }
       }
       for (const Thruster<R>& t : E.thrusters) {
         *o++ = t.active; *o++ = t.pos.x; *o++ = t.pos.y; *o++ = t.power;
-        *o++ = std::sin(t.angle); *o++ = std::cos(t.angle);
+        { V2<R> u = unit(t.angle); *o++ = u.y; *o++ = u.x; }
       }
     }
     return 0;
@@ -913,6 +975,14 @@ int ko_step(void* h, const double* actions, int n_steps, int n_threads) {
 }
 int ko_obs_dim(void* h) { return static_cast<BatchBase*>(h)->obs_dim(); }
 int ko_obs(void* h, double* out) { return static_cast<BatchBase*>(h)->obs(out); }
+
+// The engine's sin, cos, tanh for unit tests: out[i] = {sin, cos, tanh}(x[i]) in fp32 or double.
+void ko_math(int use_double, const double* x, long n, double* sn, double* cs, double* th) {
+  for (long i = 0; i < n; ++i) {
+    if (use_double) { double s, c; Fn<double>::sincos(x[i], s, c); sn[i] = s; cs[i] = c; th[i] = Fn<double>::tanh(x[i]); }
+    else { float s, c; Fn<float>::sincos((float)x[i], s, c); sn[i] = s; cs[i] = c; th[i] = Fn<float>::tanh((float)x[i]); }
+  }
+}
 
 // Canonical visiting order of the shape pairs: writes a[], b[], round[]; returns the number of pairs.
 int ko_schedule(int N, int* a, int* b, int* round) {

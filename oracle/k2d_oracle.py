@@ -58,6 +58,7 @@ def lib():
         L.ko_obs_dim.argtypes = [ctypes.c_void_p]
         L.ko_obs.argtypes = [ctypes.c_void_p, dp]
         L.ko_schedule.argtypes = [ctypes.c_int, ip, ip, ip]
+        L.ko_math.argtypes = [ctypes.c_int, dp, ctypes.c_long, dp, dp, dp]
         L.ko_manifold_cc.argtypes = [ctypes.c_int, dp, ctypes.c_double, dp, ctypes.c_double, dp]
         L.ko_manifold_pc.argtypes = [ctypes.c_int, ctypes.c_int, dp, dp, ctypes.c_double, dp]
         L.ko_manifold_pp.argtypes = [ctypes.c_int, ctypes.c_int, dp, ctypes.c_int, dp, ctypes.c_double, dp]
@@ -198,3 +199,11 @@ def manifold_pp(poly_a, poly_b, tie_eps=1e-3, dtype="f64"):
     out = np.zeros(11)
     lib().ko_manifold_pp(int(dtype == "f64"), a.shape[0], _dptr(a), b.shape[0], _dptr(b), float(tie_eps), _dptr(out))
     return _unpack(out)
+
+
+def math_fns(x, dtype="f32"):
+    """The engine's (sin, cos, tanh) evaluated elementwise in the given precision."""
+    x = _f64(x).reshape(-1)
+    sn, cs, th = np.empty_like(x), np.empty_like(x), np.empty_like(x)
+    lib().ko_math(int(dtype == "f64"), _dptr(x), x.size, _dptr(sn), _dptr(cs), _dptr(th))
+    return sn, cs, th

@@ -1,0 +1,1124 @@
+// k2d.hip -- MI355X (gfx950) implementation of the batched 2D rigid-body step behind include/k2d.h.
+//
+// What is computed: the main loop of the paper's physics engine (Appendix A, Algorithm 1) for every
+// environment of a batch: gravity, collision manifolds for all shape pairs (A.3.1-A.3.4), motors (A.5),
+// thrusters (A.6), warm starting (A.7), `n_iters` sweeps of joint constraints (A.4) then collision
+// constraints (A.3.5-A.3.7), the Euler step, and the positional corrections (A.3.7, A.4.1).
+//
+// How it is mapped onto CDNA4:
+//   * One environment is owned by a group of G consecutive lanes (G = 4 or 8), so a 64-wide wavefront
+//     steps 16 or 8 environments; a workgroup is exactly one wavefront, which makes every barrier a
+//     wave-local fence and lets the hardware place wavefronts on CUs freely.
+//   * The whole scene of an environment lives in LDS for the entire launch (all steps, substeps and
+//     solver sweeps); HBM is touched when the launch begins (one coalesced read of the record), once per
+//     step for the actions, and when it ends.  Lanes of a group exchange body velocities through LDS.
+//   * Collision constraints are visited in a round-robin tournament order: the pairs of one round touch
+//     disjoint shapes, lane k of the group owns pair k of every round, so a whole round is solved in
+//     parallel and is bit-identical to the sequential Gauss-Seidel sweep in that order (the sequential
+//     end of the speed/stability trade-off of A.8, reached without the paper's batch-of-16 compromise).
+//     Each environment walks only its own non-empty rounds.
+//   * Active manifolds of a substep are kept as records in a small LDS pool per environment; the rare
+//     environment with more active pairs than the pool holds spills the excess records to its HBM record.
+//   * Joints are solved in index order per shape (A.8: sequential); joints that share no shape are
+//     independent, so they are grouped into dependency levels once per launch and lane j solves joint j.
+//
+// Nothing here is a dense contraction: no MFMA.  Arithmetic is fp32; the kernel is compiled without
+// contraction of a*b+c so that it rounds like a plain evaluation of the formulas.
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+#include <new>
+
+#include "k2d.h"
+
+namespace {
+
+constexpr int kRecW = 25;  // words of one active-pair record (see PairRec)
+
+constexpr int align_up(int x, int a) { return (x + a - 1) / a * a; }
+
+// Word offsets of one environment record (documented in k2d.h).
+constexpr k2d_layout make_layout(int P, int C, int J, int T) {
+  k2d_layout L{};
+  const int N = P + C;
+  L.n_shapes = N;
+  L.n_pairs = N * (N - 1) / 2;
+  int o = 0;
+  L.pos_x = o; o += N;
+  L.pos_y = o; o += N;
+  L.theta = o; o += N;
+  L.vel_x = o; o += N;
+  L.vel_y = o; o += N;
+  L.omega = o; o += N;
+  L.inv_mass = o; o += N;
+  L.inv_inertia = o; o += N;
+  L.friction = o; o += N;
+  L.restitution = o; o += N;
+  L.density = o; o += N;
+  L.shape_flags = o; o += N;
+  L.n_verts = o; o += P;
+  L.verts = o; o += 8 * P;
+  L.radius = o; o += C;
+  L.joint_flags = o; o += J;
+  L.joint_a = o; o += J;
+  L.joint_b = o; o += J;
+  L.anchor_a_x = o; o += J;
+  L.anchor_a_y = o; o += J;
+  L.anchor_b_x = o; o += J;
+  L.anchor_b_y = o; o += J;
+  L.theta_f = o; o += J;
+  L.motor_speed = o; o += J;
+  L.motor_power = o; o += J;
+  L.acc_x = o; o += J;
+  L.acc_y = o; o += J;
+  L.acc_ang = o; o += J;
+  L.thr_flags = o; o += T;
+  L.thr_body = o; o += T;
+  L.thr_pos_x = o; o += T;
+  L.thr_pos_y = o; o += T;
+  L.thr_angle = o; o += T;
+  L.thr_power = o; o += T;
+  L.scene_words = o;
+  o = align_up(o, 4);
+  L.lambda = o; o += 4 * L.n_pairs;
+  L.pair_state = o; o += (L.n_pairs + 3) / 4;
+  L.state_words = o;
+  L.obs_dim = P * 23 + C * 15 + J * 11 + T * 6;
+  return L;
+}
+
+// Compile-time description of one capacity class and of its LDS image.
+template <int P_, int C_, int J_, int T_, int POOL_>
+struct Cfg {
+  static constexpr int P = P_, C = C_, J = J_, T = T_, POOL = POOL_;
+  static constexpr int N = P + C, NP = N * (N - 1) / 2, A = J + T;
+  static constexpr int M = N + (N & 1);   // tournament size (an odd N gets a phantom that sits out)
+  static constexpr int R = M - 1;         // rounds
+  static constexpr int PPR = M / 2;       // pairs per round
+  static constexpr int G = PPR <= 4 ? 4 : 8;   // lanes per environment
+  static constexpr int EPW = 64 / G;           // environments per wavefront
+  static_assert(PPR <= 8 && J <= G && T <= G && N <= 2 * G && R <= 15, "capacity class does not fit the lane mapping");
+  static constexpr k2d_layout L = make_layout(P, C, J, T);
+  // HBM record: state words, then room for the pair records that do not fit the LDS pool
+  static constexpr int SPILL = (NP > POOL ? NP - POOL : 0);
+  static constexpr int G_SPILL = align_up(L.state_words, 4);
+  static constexpr int REC_WORDS = align_up(G_SPILL + SPILL * kRecW, 32);
+  // LDS image of one environment: scene words, then derived data
+  static constexpr int X_COS = align_up(L.scene_words, 2);
+  static constexpr int X_SIN = X_COS + N;
+  static constexpr int X_BRAD = X_SIN + N;       // bounding radius of every shape
+  static constexpr int X_JOINED = X_BRAD + N;    // bit j of word i: shapes i, j joined by a live joint
+  static constexpr int X_WV = align_up(X_JOINED + N, 2);   // world vertices, float2 [4][P]
+  static constexpr int X_WN = X_WV + 8 * P;                // outward unit edge normals, float2 [4][P]
+  static constexpr int X_TABLE = X_WN + 8 * P;             // bytes [R][G]: pool index of pair (r, k)
+  static constexpr int X_POOL = X_TABLE + (R * G + 3) / 4;
+  static constexpr int LDS_WORDS = X_POOL + POOL * kRecW;
+  // stride = odd multiple of G words: the same word of different environments falls into different banks
+  static constexpr int LDS_STRIDE = align_up(LDS_WORDS - G, 2 * G) + G;
+  static_assert(LDS_STRIDE >= LDS_WORDS && (LDS_STRIDE / G) % 2 == 1, "stride rule");
+  static constexpr int LDS_BYTES = LDS_STRIDE * EPW * 4;
+};
+
+struct Params {   // device copy of k2d_params with the substep precomputed
+  float h, gravity_y;
+  int n_substeps, n_iters, warm_start;
+  float alpha, beta, gamma, rho, slop, rest_thr;
+  int clip_thr;
+  float joint_alpha, joint_beta, tie_eps;
+};
+
+__device__ __forceinline__ int f2i(float f) { return __float_as_int(f); }
+__device__ __forceinline__ float i2f(int i) { return __int_as_float(i); }
+
+// One active pair of the current substep.  Body indices and per-point activity are packed in `ab`.
+struct PairRec {
+  float nx, ny, mu, corr;        // unit normal a->b; friction coefficient; positional-correction length
+  int ab;                        // a | b<<8 | active0<<16 | active1<<17
+  float rax[2], ray[2], rbx[2], rby[2], mass_n[2], mass_t[2], bias[2], rest[2], lam_n[2], lam_t[2];
+};
+
+__device__ __forceinline__ void rec_store(float* p, const PairRec& r) {
+  p[0] = r.nx; p[1] = r.ny; p[2] = r.mu; p[3] = r.corr; p[4] = i2f(r.ab);
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    float* q = p + 5 + 10 * k;
+    q[0] = r.rax[k]; q[1] = r.ray[k]; q[2] = r.rbx[k]; q[3] = r.rby[k]; q[4] = r.mass_n[k];
+    q[5] = r.mass_t[k]; q[6] = r.bias[k]; q[7] = r.rest[k]; q[8] = r.lam_n[k]; q[9] = r.lam_t[k];
+  }
+}
+__device__ __forceinline__ void rec_load(const float* p, PairRec& r) {
+  r.nx = p[0]; r.ny = p[1]; r.mu = p[2]; r.corr = p[3]; r.ab = f2i(p[4]);
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const float* q = p + 5 + 10 * k;
+    r.rax[k] = q[0]; r.ray[k] = q[1]; r.rbx[k] = q[2]; r.rby[k] = q[3]; r.mass_n[k] = q[4];
+    r.mass_t[k] = q[5]; r.bias[k] = q[6]; r.rest[k] = q[7]; r.lam_n[k] = q[8]; r.lam_t[k] = q[9];
+  }
+}
+
+// Collision manifold (Table 2) of one pair: unit normal from a to b, up to two points.
+struct Manifold {
+  float nx = 0.f, ny = 0.f;
+  float px[2] = {0.f, 0.f}, py[2] = {0.f, 0.f}, pen[2] = {0.f, 0.f};
+  bool valid[2] = {false, false};
+};
+
+template <class K>
+struct Step {
+  static constexpr k2d_layout L = K::L;
+  static constexpr int N = K::N, P = K::P, G = K::G;
+
+  // ---- LDS accessors (E = base of this environment's image) ----
+  static __device__ __forceinline__ float2 wv(const float* E, int i, int p) {
+    return *reinterpret_cast<const float2*>(E + K::X_WV + 2 * (i * P + p));
+  }
+  static __device__ __forceinline__ float2 wn(const float* E, int i, int p) {
+    return *reinterpret_cast<const float2*>(E + K::X_WN + 2 * (i * P + p));
+  }
+
+  // Pair k of round r of the round-robin tournament; returns false for the phantom's pair.
+  static __device__ __forceinline__ bool sched_pair(int r, int k, int& a, int& b) {
+    int x, y;
+    if (k == 0) {
+      x = K::M - 1;
+      y = r;
+    } else {
+      x = r + k;
+      if (x >= K::M - 1) x -= K::M - 1;
+      y = r - k;
+      if (y < 0) y += K::M - 1;
+    }
+    a = min(x, y);
+    b = max(x, y);
+    return k < K::PPR && b < N;
+  }
+  static __device__ __forceinline__ int pair_index(int a, int b) { return a * (2 * N - a - 1) / 2 + (b - a - 1); }
+
+  // ---- A.3.2: circle a, circle b ----
+  static __device__ __forceinline__ void manifold_cc(float pax, float pay, float ra, float pbx, float pby, float rb,
+                                                     Manifold& m) {
+    float dx = pbx - pax, dy = pby - pay;
+    float len = sqrtf(dx * dx + dy * dy);
+    bool ok = len > 1e-9f;
+    m.nx = ok ? dx / len : 1.f;
+    m.ny = ok ? dy / len : 0.f;
+    m.px[0] = pax + ra * m.nx;
+    m.py[0] = pay + ra * m.ny;
+    m.pen[0] = ra + rb - len;
+    m.valid[0] = true;
+  }
+
+  // ---- A.3.3: polygon a (index pa in the world arrays), circle b ----
+  static __device__ __forceinline__ void manifold_pc(const float* E, int pa, int na, float cx, float cy, float rb,
+                                                     Manifold& m) {
+    float best_d2 = INFINITY, qx = 0.f, qy = 0.f;
+    float smax = -INFINITY, snx = 0.f, sny = 0.f;
+    float2 v = wv(E, 0, pa);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (i < na) {
+        int i1 = (i + 1 == na) ? 0 : i + 1;
+        float2 v1 = wv(E, i1, pa);
+        float2 nr = wn(E, i, pa);
+        float ex = v1.x - v.x, ey = v1.y - v.y;
+        float rx = cx - v.x, ry = cy - v.y;
+        float t = (rx * ex + ry * ey) / (ex * ex + ey * ey);
+        t = fminf(fmaxf(t, 0.f), 1.f);
+        float qix = v.x + t * ex, qiy = v.y + t * ey;
+        float dqx = cx - qix, dqy = cy - qiy;
+        float d2 = dqx * dqx + dqy * dqy;
+        if (d2 < best_d2) { best_d2 = d2; qx = qix; qy = qiy; }
+        float s = nr.x * rx + nr.y * ry;
+        if (s > smax) { smax = s; snx = nr.x; sny = nr.y; }
+        v = v1;
+      }
+    }
+    if (smax <= 0.f) {   // centre inside the polygon: the face of largest signed distance
+      m.nx = snx; m.ny = sny;
+      m.pen[0] = rb - smax;
+      m.px[0] = cx - smax * snx;
+      m.py[0] = cy - smax * sny;
+    } else {
+      float dist = sqrtf(best_d2);
+      float dqx = cx - qx, dqy = cy - qy;
+      m.nx = dqx / dist; m.ny = dqy / dist;
+      m.pen[0] = rb - dist;
+      m.px[0] = qx; m.py[0] = qy;
+    }
+    m.valid[0] = true;
+  }
+
+  // Largest over X's faces of the smallest signed distance of Y's vertices to the face (A.3.4).
+  static __device__ __forceinline__ void face_query(const float* E, int px, int nx_, const float2 (&yw)[4], int ny_,
+                                                    float& best, int& idx) {
+    best = -INFINITY;
+    idx = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (i < nx_) {
+        float2 nr = wn(E, i, px);
+        float2 w = wv(E, i, px);
+        float smin = INFINITY;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          if (k < ny_) {
+            float s = nr.x * (yw[k].x - w.x) + nr.y * (yw[k].y - w.y);
+            smin = (s < smin) ? s : smin;
+          }
+        }
+        if (smin > best) { best = smin; idx = i; }
+      }
+    }
+  }
+
+  // ---- A.3.4: polygon a, polygon b (indices in the world arrays) ----
+  static __device__ __forceinline__ void manifold_pp(const float* E, int pa, int na, int pb, int nb, float tie_eps,
+                                                     Manifold& m) {
+    float2 aw[4], bw[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { aw[i] = wv(E, i, pa); bw[i] = wv(E, i, pb); }
+    float sa, sb;
+    int ia, ib;
+    face_query(E, pa, na, bw, nb, sa, ia);
+    face_query(E, pb, nb, aw, na, sb, ib);
+    if (fmaxf(sa, sb) >= 0.f) return;   // a separating axis exists
+    bool ref_b = sb > sa + tie_eps;
+    int pr = ref_b ? pb : pa, nr_ = ref_b ? nb : na, ir = ref_b ? ib : ia;
+    int pi = ref_b ? pa : pb, ni = ref_b ? na : nb;
+    float2 nref = wn(E, ir, pr);
+    float2 r1 = wv(E, ir, pr);
+    float2 r2 = wv(E, (ir + 1 == nr_) ? 0 : ir + 1, pr);
+    int jinc = 0;
+    float dmin = INFINITY;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (j < ni) {
+        float2 nj = wn(E, j, pi);
+        float d = nj.x * nref.x + nj.y * nref.y;
+        if (d < dmin) { dmin = d; jinc = j; }
+      }
+    }
+    float2 v0 = wv(E, jinc, pi);
+    float2 v1 = wv(E, (jinc + 1 == ni) ? 0 : jinc + 1, pi);
+    float tx = -nref.y, ty = nref.x;
+    float u0 = tx * (v0.x - r1.x) + ty * (v0.y - r1.y);
+    float u1 = tx * (v1.x - r1.x) + ty * (v1.y - r1.y);
+    float len = tx * (r2.x - r1.x) + ty * (r2.y - r1.y);
+    if ((u0 < 0.f && u1 < 0.f) || (u0 > len && u1 > len)) return;
+    m.nx = ref_b ? -nref.x : nref.x;
+    m.ny = ref_b ? -nref.y : nref.y;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      float uk = k ? u1 : u0;
+      float uc = fminf(fmaxf(uk, 0.f), len);
+      float x = k ? v1.x : v0.x, y = k ? v1.y : v0.y;
+      if (uc != uk) {
+        float s = (uc - u0) / (u1 - u0);
+        x = v0.x + s * (v1.x - v0.x);
+        y = v0.y + s * (v1.y - v0.y);
+      }
+      m.px[k] = x; m.py[k] = y;
+      m.pen[k] = -(nref.x * (x - r1.x) + nref.y * (y - r1.y));
+      m.valid[k] = true;
+    }
+  }
+
+  // Relative velocity of the contact points, v_a + w_a x r_a - v_b - w_b x r_b (A.3.5).
+  static __device__ __forceinline__ void rel_vel(float vax, float vay, float wa, float rax, float ray, float vbx,
+                                                 float vby, float wb, float rbx, float rby, float& x, float& y) {
+    x = vax + (-wa * ray) - vbx - (-wb * rby);
+    y = vay + (wa * rax) - vby - (wb * rbx);
+  }
+
+  // One visit of an active pair in a solver sweep: per point, normal impulse then friction impulse,
+  // accumulated and clamped (A.3.5, A.3.6, A.7).  Velocities are read from and written to LDS.
+  static __device__ __forceinline__ void solve_pair(float* E, PairRec& rc) {
+    const int a = rc.ab & 0xff, b = (rc.ab >> 8) & 0xff;
+    float vax = E[L.vel_x + a], vay = E[L.vel_y + a], wa = E[L.omega + a];
+    float vbx = E[L.vel_x + b], vby = E[L.vel_y + b], wb = E[L.omega + b];
+    const float ima = E[L.inv_mass + a], iia = E[L.inv_inertia + a];
+    const float imb = E[L.inv_mass + b], iib = E[L.inv_inertia + b];
+    const float tx = -rc.ny, ty = rc.nx;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      if ((rc.ab >> (16 + k)) & 1) {
+        float rx, ry;
+        rel_vel(vax, vay, wa, rc.rax[k], rc.ray[k], vbx, vby, wb, rc.rbx[k], rc.rby[k], rx, ry);
+        float vn = rc.nx * rx + rc.ny * ry;
+        float dl = rc.mass_n[k] * (vn + rc.rest[k] + rc.bias[k]);
+        float ln = fmaxf(rc.lam_n[k] + dl, 0.f);
+        dl = ln - rc.lam_n[k];
+        rc.lam_n[k] = ln;
+        float jx = (-dl) * rc.nx, jy = (-dl) * rc.ny;
+        vax = vax + ima * jx; vay = vay + ima * jy;
+        wa = wa + iia * (rc.rax[k] * jy - rc.ray[k] * jx);
+        vbx = vbx + imb * (-jx); vby = vby + imb * (-jy);
+        wb = wb + iib * (rc.rbx[k] * (-jy) - rc.rby[k] * (-jx));
+        rel_vel(vax, vay, wa, rc.rax[k], rc.ray[k], vbx, vby, wb, rc.rbx[k], rc.rby[k], rx, ry);
+        float vt = tx * rx + ty * ry;
+        float dt_ = -rc.mass_t[k] * vt;
+        float lim = rc.mu * ln;
+        float lt = fminf(fmaxf(rc.lam_t[k] + dt_, -lim), lim);
+        dt_ = lt - rc.lam_t[k];
+        rc.lam_t[k] = lt;
+        float fx = dt_ * tx, fy = dt_ * ty;
+        vax = vax + ima * fx; vay = vay + ima * fy;
+        wa = wa + iia * (rc.rax[k] * fy - rc.ray[k] * fx);
+        vbx = vbx + imb * (-fx); vby = vby + imb * (-fy);
+        wb = wb + iib * (rc.rbx[k] * (-fy) - rc.rby[k] * (-fx));
+      }
+    }
+    E[L.vel_x + a] = vax; E[L.vel_y + a] = vay; E[L.omega + a] = wa;
+    E[L.vel_x + b] = vbx; E[L.vel_y + b] = vby; E[L.omega + b] = wb;
+  }
+
+  // Warm starting of one pair (A.7): re-apply the kept accumulated impulses.
+  static __device__ __forceinline__ void warm_pair(float* E, const PairRec& rc) {
+    const int a = rc.ab & 0xff, b = (rc.ab >> 8) & 0xff;
+    float vax = E[L.vel_x + a], vay = E[L.vel_y + a], wa = E[L.omega + a];
+    float vbx = E[L.vel_x + b], vby = E[L.vel_y + b], wb = E[L.omega + b];
+    const float ima = E[L.inv_mass + a], iia = E[L.inv_inertia + a];
+    const float imb = E[L.inv_mass + b], iib = E[L.inv_inertia + b];
+    const float tx = -rc.ny, ty = rc.nx;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      if ((rc.ab >> (16 + k)) & 1) {
+        float jx = (-rc.lam_n[k]) * rc.nx + rc.lam_t[k] * tx;
+        float jy = (-rc.lam_n[k]) * rc.ny + rc.lam_t[k] * ty;
+        vax = vax + ima * jx; vay = vay + ima * jy;
+        wa = wa + iia * (rc.rax[k] * jy - rc.ray[k] * jx);
+        vbx = vbx + imb * (-jx); vby = vby + imb * (-jy);
+        wb = wb + iib * (rc.rbx[k] * (-jy) - rc.rby[k] * (-jx));
+      }
+    }
+    E[L.vel_x + a] = vax; E[L.vel_y + a] = vay; E[L.omega + a] = wa;
+    E[L.vel_x + b] = vbx; E[L.vel_y + b] = vby; E[L.omega + b] = wb;
+  }
+};
+
+// Walks, for every environment of the wavefront, the rounds in which that environment has an active
+// pair, in round order; lane k of the group runs `f(r)` if its own pair of round r is active.  A fence
+// follows every round, so the next round sees this round's LDS writes.
+template <class F>
+__device__ __forceinline__ void for_each_round(unsigned env_rounds, unsigned my_rounds, F&& f) {
+  unsigned rm = env_rounds;
+  while (__any(rm != 0u)) {
+    if (rm != 0u) {
+      int r = __ffs(rm) - 1;
+      rm &= rm - 1u;
+      if ((my_rounds >> r) & 1u) f(r);
+    }
+    __syncthreads();
+  }
+}
+
+template <class K>
+__global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state, const float* __restrict__ actions,
+                                                      int n_envs, int n_steps, Params prm) {
+  using S = Step<K>;
+  constexpr k2d_layout L = K::L;
+  constexpr int N = K::N, P = K::P, J = K::J, T = K::T, G = K::G, R = K::R;
+  extern __shared__ __align__(16) float lds[];
+
+  const int lane = threadIdx.x;
+  const int g = lane / G, k = lane % G;
+  const int env0 = blockIdx.x * K::EPW;
+  const int env = env0 + g;
+  const bool env_ok = env < n_envs;
+  float* E = lds + g * K::LDS_STRIDE;
+  float* Rg = state + (size_t)(env_ok ? env : 0) * K::REC_WORDS;   // this environment's HBM record
+
+  // ---- load the scene description into LDS, one environment after the other, 64 words at a time ----
+  for (int e = 0; e < K::EPW; ++e) {
+    float* dst = lds + e * K::LDS_STRIDE;
+    if (env0 + e < n_envs) {
+      const float* src = state + (size_t)(env0 + e) * K::REC_WORDS;
+      for (int w = lane; w < L.scene_words; w += 64) dst[w] = src[w];
+    } else {
+      for (int w = lane; w < L.scene_words; w += 64) dst[w] = 0.f;   // all-inactive padding environment
+    }
+  }
+  __syncthreads();
+
+  // ---- per-launch derived data ----
+  for (int i = k; i < N; i += G) {
+    float sn, cs;
+    sincosf(E[L.theta + i], &sn, &cs);
+    E[K::X_COS + i] = cs;
+    E[K::X_SIN + i] = sn;
+    float br;
+    if (i < P) {
+      int nv = f2i(E[L.n_verts + i]);
+      br = 0.f;
+      for (int v = 0; v < 4; ++v) {
+        float lx = E[L.verts + (2 * v) * P + i], ly = E[L.verts + (2 * v + 1) * P + i];
+        if (v < nv) br = fmaxf(br, sqrtf(lx * lx + ly * ly));
+      }
+    } else {
+      br = E[L.radius + (i - P)];
+    }
+    E[K::X_BRAD + i] = br;
+    E[K::X_JOINED + i] = i2f(0);
+  }
+  __syncthreads();
+  // joints: lane j of the group owns joint j for the whole launch
+  bool j_live = false, j_fixed = false, j_motor = false;
+  int ja = 0, jb = 0;
+  float j_aax = 0.f, j_aay = 0.f, j_abx = 0.f, j_aby = 0.f, j_thf = 0.f, j_speed = 0.f, j_power = 0.f;
+  float j_accx = 0.f, j_accy = 0.f, j_acca = 0.f;
+  if (k < J) {
+    int fl = f2i(E[L.joint_flags + k]);
+    ja = f2i(E[L.joint_a + k]);
+    jb = f2i(E[L.joint_b + k]);
+    bool idx_ok = ja >= 0 && ja < N && jb >= 0 && jb < N && ja != jb;
+    if (!idx_ok) { ja = 0; jb = 0; }
+    j_fixed = (fl >> 1) & 1;
+    j_motor = (fl >> 2) & 1;
+    j_live = (fl & 1) && idx_ok && (f2i(E[L.shape_flags + ja]) & 1) && (f2i(E[L.shape_flags + jb]) & 1) &&
+             (E[L.inv_mass + ja] + E[L.inv_mass + jb]) > 0.f;
+    j_aax = E[L.anchor_a_x + k]; j_aay = E[L.anchor_a_y + k];
+    j_abx = E[L.anchor_b_x + k]; j_aby = E[L.anchor_b_y + k];
+    j_thf = E[L.theta_f + k]; j_speed = E[L.motor_speed + k]; j_power = E[L.motor_power + k];
+    j_accx = E[L.acc_x + k]; j_accy = E[L.acc_y + k]; j_acca = E[L.acc_ang + k];
+    if (!j_live) { j_accx = 0.f; j_accy = 0.f; j_acca = 0.f; }
+    if (!j_fixed) j_acca = 0.f;
+    if (j_live) {   // A.4: joined shapes do not collide
+      atomicOr(reinterpret_cast<unsigned*>(E + K::X_JOINED + ja), 1u << jb);
+      atomicOr(reinterpret_cast<unsigned*>(E + K::X_JOINED + jb), 1u << ja);
+    }
+    E[L.joint_flags + k] = i2f((fl & 7) | (j_live ? 8 : 0));
+  }
+  __syncthreads();
+  // dependency levels of the joints: a joint runs one level after the last earlier joint that shares a
+  // shape with it, so joints sharing a shape keep their index order and the others run side by side
+  int j_level = 0, n_levels = 0;
+  {
+    unsigned long long last = 0ull;   // 4 bits per shape: next free level
+    for (int q = 0; q < J; ++q) {
+      int fl = f2i(E[L.joint_flags + q]);
+      if (fl & 8) {
+        int a = f2i(E[L.joint_a + q]), b = f2i(E[L.joint_b + q]);
+        int la = (int)((last >> (4 * a)) & 15ull), lb = (int)((last >> (4 * b)) & 15ull);
+        int lv = max(la, lb);
+        if (q == k) j_level = lv;
+        n_levels = max(n_levels, lv + 1);
+        last &= ~((15ull << (4 * a)) | (15ull << (4 * b)));
+        last |= ((unsigned long long)(lv + 1) << (4 * a)) | ((unsigned long long)(lv + 1) << (4 * b));
+      }
+    }
+  }
+  // levels are per environment; the wavefront walks as many as its deepest environment has
+  int wave_levels = 0;
+  for (int lv = 1; lv <= J; ++lv)
+    if (__any(n_levels >= lv)) wave_levels = lv;
+  // thrusters: lane t of the group owns thruster t
+  bool t_live = false;
+  int t_body = 0;
+  float t_px = 0.f, t_py = 0.f, t_dx = 0.f, t_dy = 0.f, t_power = 0.f;
+  if (k < T) {
+    int fl = f2i(E[L.thr_flags + k]);
+    t_body = f2i(E[L.thr_body + k]);
+    bool idx_ok = t_body >= 0 && t_body < N;
+    if (!idx_ok) t_body = 0;
+    t_live = (fl & 1) && idx_ok && (f2i(E[L.shape_flags + t_body]) & 1);
+    t_px = E[L.thr_pos_x + k]; t_py = E[L.thr_pos_y + k];
+    sincosf(E[L.thr_angle + k], &t_dy, &t_dx);
+    t_power = E[L.thr_power + k];
+  }
+  // pairs: lane k owns pair k of every round; eligibility is fixed for the launch
+  unsigned elig = 0u, prev_bits = 0u;
+  for (int r = 0; r < R; ++r) {
+    int a, b;
+    if (S::sched_pair(r, k, a, b)) {
+      bool ok = (f2i(E[L.shape_flags + a]) & 1) && (f2i(E[L.shape_flags + b]) & 1) &&
+                !((f2i(E[K::X_JOINED + a]) >> b) & 1) && (E[L.inv_mass + a] + E[L.inv_mass + b]) > 0.f;
+      if (ok) {
+        elig |= 1u << r;
+        if (env_ok) {
+          const unsigned char* ps = reinterpret_cast<const unsigned char*>(Rg + L.pair_state);
+          prev_bits |= (unsigned)(ps[S::pair_index(a, b)] & 3) << (2 * r);
+        }
+      }
+    }
+  }
+  unsigned char* table = reinterpret_cast<unsigned char*>(E + K::X_TABLE);
+  float* pool = E + K::X_POOL;
+  float* spill = Rg + K::G_SPILL;
+  const float h = prm.h;
+  const int A = J + T;
+
+  for (int step = 0; step < n_steps; ++step) {
+    float act_m = 0.f, act_t = 0.f;
+    if (env_ok) {
+      const float* ap = actions + ((size_t)step * n_envs + env) * A;
+      if (k < J) act_m = ap[k];
+      if (k < T) act_t = ap[J + k];
+    }
+    if (prm.clip_thr) act_t = fminf(fmaxf(act_t, 0.f), 1.f);
+
+    for (int sub = 0; sub < prm.n_substeps; ++sub) {
+      // ---- gravity (Alg. 1) and world-frame polygons ----
+      for (int i = k; i < N; i += G) {
+        bool act = f2i(E[L.shape_flags + i]) & 1;
+        if (act && E[L.inv_mass + i] > 0.f) E[L.vel_y + i] = E[L.vel_y + i] + prm.gravity_y * h;
+        if (i < P) {
+          float cs = E[K::X_COS + i], sn = E[K::X_SIN + i], px = E[L.pos_x + i], py = E[L.pos_y + i];
+          int nv = f2i(E[L.n_verts + i]);
+          float wx[4], wy[4];
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            float lx = E[L.verts + (2 * v) * P + i], ly = E[L.verts + (2 * v + 1) * P + i];
+            wx[v] = px + (cs * lx - sn * ly);
+            wy[v] = py + (sn * lx + cs * ly);
+          }
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            int v1 = (v + 1 == nv) ? 0 : ((v + 1) & 3);
+            float ex = wx[v1] - wx[v], ey = wy[v1] - wy[v];
+            float len = sqrtf(ex * ex + ey * ey);
+            *reinterpret_cast<float2*>(E + K::X_WV + 2 * (v * P + i)) = make_float2(wx[v], wy[v]);
+            *reinterpret_cast<float2*>(E + K::X_WN + 2 * (v * P + i)) = make_float2(ey / len, -ex / len);
+          }
+        }
+      }
+      __syncthreads();
+
+      // ---- joint constants of this substep; motor and thruster impulses from the same velocities ----
+      float j_rax = 0.f, j_ray = 0.f, j_rbx = 0.f, j_rby = 0.f, j_k11 = 0.f, j_k12 = 0.f, j_k22 = 0.f;
+      float j_idet = 0.f, j_bx = 0.f, j_by = 0.f, j_angm = 0.f, j_angb = 0.f, motor = 0.f;
+      float j_ima = 0.f, j_iia = 0.f, j_imb = 0.f, j_iib = 0.f;
+      if (k < J && j_live) {
+        if (!prm.warm_start) { j_accx = 0.f; j_accy = 0.f; j_acca = 0.f; }
+        j_ima = E[L.inv_mass + ja]; j_iia = E[L.inv_inertia + ja];
+        j_imb = E[L.inv_mass + jb]; j_iib = E[L.inv_inertia + jb];
+        float ca = E[K::X_COS + ja], sa = E[K::X_SIN + ja], cb = E[K::X_COS + jb], sb = E[K::X_SIN + jb];
+        j_rax = ca * j_aax - sa * j_aay; j_ray = sa * j_aax + ca * j_aay;
+        j_rbx = cb * j_abx - sb * j_aby; j_rby = sb * j_abx + cb * j_aby;
+        float ms = j_ima + j_imb;
+        j_k11 = ms + j_iia * j_ray * j_ray + j_iib * j_rby * j_rby;
+        j_k22 = ms + j_iia * j_rax * j_rax + j_iib * j_rbx * j_rbx;
+        j_k12 = -j_iia * j_rax * j_ray - j_iib * j_rbx * j_rby;
+        j_idet = 1.f / (j_k11 * j_k22 - j_k12 * j_k12);
+        float sx = (E[L.pos_x + ja] + j_rax) - (E[L.pos_x + jb] + j_rbx);
+        float sy = (E[L.pos_y + ja] + j_ray) - (E[L.pos_y + jb] + j_rby);
+        j_bx = prm.joint_alpha * sx; j_by = prm.joint_alpha * sy;
+        float is = j_iia + j_iib;
+        j_angm = (is > 0.f) ? 1.f / is : 0.f;
+        j_angb = prm.gamma * (E[L.theta + ja] - E[L.theta + jb] - j_thf);
+        if (!j_fixed && j_motor) {   // A.5
+          float arg = (E[L.omega + ja] - E[L.omega + jb] - j_speed * act_m) * prm.rho;
+          motor = j_power * tanhf(arg) * h;
+        }
+      }
+      float t_ix = 0.f, t_iy = 0.f, t_rx = 0.f, t_ry = 0.f;
+      if (k < T && t_live) {   // A.6
+        float cs = E[K::X_COS + t_body], sn = E[K::X_SIN + t_body];
+        float dx = cs * t_dx - sn * t_dy, dy = sn * t_dx + cs * t_dy;
+        t_rx = cs * t_px - sn * t_py; t_ry = sn * t_px + cs * t_py;
+        float f = t_power * act_t * h;
+        t_ix = f * dx; t_iy = f * dy;
+      }
+      __syncthreads();
+      for (int lv = 0; lv < wave_levels; ++lv) {
+        if (k < J && j_live && j_level == lv && motor != 0.f) {
+          E[L.omega + ja] = E[L.omega + ja] - j_iia * motor;
+          E[L.omega + jb] = E[L.omega + jb] + j_iib * motor;
+        }
+        __syncthreads();
+      }
+      for (int t = 0; t < T; ++t) {
+        if (k == t && t_live) {
+          float im = E[L.inv_mass + t_body], ii = E[L.inv_inertia + t_body];
+          E[L.vel_x + t_body] = E[L.vel_x + t_body] + im * t_ix;
+          E[L.vel_y + t_body] = E[L.vel_y + t_body] + im * t_iy;
+          E[L.omega + t_body] = E[L.omega + t_body] + ii * (t_rx * t_iy - t_ry * t_ix);
+        }
+        __syncthreads();
+      }
+
+      // ---- collision manifolds of all eligible pairs (A.3.1-A.3.4) and their substep constants ----
+      unsigned my_rounds = 0u, new_bits = 0u;
+      int pool_base = 0;
+      for (int r = 0; r < R; ++r) {
+        Manifold m;
+        int a = 0, b = 0;
+        bool cand = (elig >> r) & 1u;
+        if (cand) {
+          S::sched_pair(r, k, a, b);
+          // bounding circles apart (with margin): no manifold point can have positive penetration
+          float dx = E[L.pos_x + b] - E[L.pos_x + a], dy = E[L.pos_y + b] - E[L.pos_y + a];
+          float rr = (E[K::X_BRAD + a] + E[K::X_BRAD + b]) * 1.0001f + 1e-5f;
+          cand = dx * dx + dy * dy <= rr * rr;
+        }
+        if (cand) {
+          if (b < P) {
+            S::manifold_pp(E, a, f2i(E[L.n_verts + a]), b, f2i(E[L.n_verts + b]), prm.tie_eps, m);
+          } else if (a < P) {
+            S::manifold_pc(E, a, f2i(E[L.n_verts + a]), E[L.pos_x + b], E[L.pos_y + b], E[L.radius + (b - P)], m);
+          } else {
+            S::manifold_cc(E[L.pos_x + a], E[L.pos_y + a], E[L.radius + (a - P)], E[L.pos_x + b], E[L.pos_y + b],
+                           E[L.radius + (b - P)], m);
+          }
+        }
+        const bool act0 = m.valid[0] && m.pen[0] > 0.f, act1 = m.valid[1] && m.pen[1] > 0.f;
+        const bool active = act0 || act1;
+        unsigned long long bal = __ballot(active);
+        unsigned envbits = (unsigned)(bal >> (g * G)) & ((1u << G) - 1u);
+        int idx = pool_base + __popc(envbits & ((1u << k) - 1u));
+        pool_base += __popc(envbits);
+        if (active) {
+          PairRec rc;
+          rc.nx = m.nx; rc.ny = m.ny;
+          rc.ab = a | (b << 8) | ((int)act0 << 16) | ((int)act1 << 17);
+          const float ima = E[L.inv_mass + a], iia = E[L.inv_inertia + a];
+          const float imb = E[L.inv_mass + b], iib = E[L.inv_inertia + b];
+          const float fa = E[L.friction + a], fb = E[L.friction + b];
+          const float e = fminf(E[L.restitution + a], E[L.restitution + b]);   // A.3.5
+          rc.mu = sqrtf(fa * fa + fb * fb);                                        // A.3.6
+          const float pax = E[L.pos_x + a], pay = E[L.pos_y + a], pbx = E[L.pos_x + b], pby = E[L.pos_y + b];
+          const float vax = E[L.vel_x + a], vay = E[L.vel_y + a], wa = E[L.omega + a];
+          const float vbx = E[L.vel_x + b], vby = E[L.vel_y + b], wb = E[L.omega + b];
+          const float tx = -m.ny, ty = m.nx;
+          float4 lam = make_float4(0.f, 0.f, 0.f, 0.f);
+          const unsigned pb = (prev_bits >> (2 * r)) & 3u;
+          if (prm.warm_start && pb != 0u)
+            lam = *reinterpret_cast<const float4*>(Rg + L.lambda + 4 * S::pair_index(a, b));
+          float pen = 0.f;
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const bool on = q ? act1 : act0;
+            rc.rax[q] = m.px[q] - pax; rc.ray[q] = m.py[q] - pay;
+            rc.rbx[q] = m.px[q] - pbx; rc.rby[q] = m.py[q] - pby;
+            float ran = rc.rax[q] * m.ny - rc.ray[q] * m.nx, rbn = rc.rbx[q] * m.ny - rc.rby[q] * m.nx;
+            float rat = rc.rax[q] * ty - rc.ray[q] * tx, rbt = rc.rbx[q] * ty - rc.rby[q] * tx;
+            float kn = ima + imb + ran * ran * iia + rbn * rbn * iib;
+            float kt = ima + imb + rat * rat * iia + rbt * rbt * iib;
+            rc.mass_n[q] = on ? 1.f / kn : 0.f;
+            rc.mass_t[q] = on ? 1.f / kt : 0.f;
+            rc.bias[q] = prm.alpha * fmaxf(m.pen[q] - prm.slop, 0.f);            // A.3.7
+            // restitution target -e*v_r (A.3.5), v_r sampled here: after motors and thrusters,
+            // before any constraint impulse; slow approaches take e = 0
+            float rx, ry;
+            S::rel_vel(vax, vay, wa, rc.rax[q], rc.ray[q], vbx, vby, wb, rc.rbx[q], rc.rby[q], rx, ry);
+            float vn0 = m.nx * rx + m.ny * ry;
+            rc.rest[q] = (vn0 > prm.rest_thr) ? e * vn0 : 0.f;
+            bool keep = prm.warm_start && on && ((pb >> q) & 1u);                 // A.7
+            rc.lam_n[q] = keep ? (q ? lam.z : lam.x) : 0.f;
+            rc.lam_t[q] = keep ? (q ? lam.w : lam.y) : 0.f;
+            if (on) pen = fmaxf(pen, m.pen[q]);
+          }
+          rc.corr = prm.beta * fmaxf(pen - prm.slop, 0.f) / (ima + imb);          // A.3.7
+          rec_store(idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW, rc);
+          table[r * G + k] = (unsigned char)idx;
+          my_rounds |= 1u << r;
+          new_bits |= ((unsigned)act0 | ((unsigned)act1 << 1)) << (2 * r);
+        }
+      }
+      prev_bits = new_bits;
+      unsigned env_rounds = my_rounds;
+      for (int o = 1; o < G; o <<= 1) env_rounds |= __shfl_xor(env_rounds, o, G);
+      __syncthreads();
+
+      // ---- warm starting (Alg. 1, A.7): collisions in canonical order, then joints ----
+      if (prm.warm_start) {
+        for_each_round(env_rounds, my_rounds, [&](int r) {
+          int idx = table[r * G + k];
+          PairRec rc;
+          rec_load(idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW, rc);
+          S::warm_pair(E, rc);
+        });
+        for (int lv = 0; lv < wave_levels; ++lv) {
+          if (k < J && j_live && j_level == lv) {
+            float wa = E[L.omega + ja], wb = E[L.omega + jb];
+            if (j_fixed) {
+              wa = wa + j_iia * j_acca;
+              wb = wb - j_iib * j_acca;
+            }
+            E[L.vel_x + ja] = E[L.vel_x + ja] + j_ima * j_accx;
+            E[L.vel_y + ja] = E[L.vel_y + ja] + j_ima * j_accy;
+            E[L.omega + ja] = wa + j_iia * (j_rax * j_accy - j_ray * j_accx);
+            E[L.vel_x + jb] = E[L.vel_x + jb] + j_imb * (-j_accx);
+            E[L.vel_y + jb] = E[L.vel_y + jb] + j_imb * (-j_accy);
+            E[L.omega + jb] = wb + j_iib * (j_rbx * (-j_accy) - j_rby * (-j_accx));
+          }
+          __syncthreads();
+        }
+      }
+
+      // ---- solver sweeps (Alg. 1): joints, then collisions ----
+      for (int it = 0; it < prm.n_iters; ++it) {
+        for (int lv = 0; lv < wave_levels; ++lv) {
+          if (k < J && j_live && j_level == lv) {
+            float vax = E[L.vel_x + ja], vay = E[L.vel_y + ja], wa = E[L.omega + ja];
+            float vbx = E[L.vel_x + jb], vby = E[L.vel_y + jb], wb = E[L.omega + jb];
+            if (j_fixed && j_angm > 0.f) {   // A.4.2
+              float d = -(wa - wb + j_angb) * j_angm;
+              wa = wa + j_iia * d;
+              wb = wb - j_iib * d;
+              j_acca = j_acca + d;
+            }
+            float cx, cy;   // A.4.1: point constraint, 2x2 solve
+            S::rel_vel(vax, vay, wa, j_rax, j_ray, vbx, vby, wb, j_rbx, j_rby, cx, cy);
+            float rx = -(cx + j_bx), ry = -(cy + j_by);
+            float jx = (j_k22 * rx - j_k12 * ry) * j_idet, jy = (j_k11 * ry - j_k12 * rx) * j_idet;
+            vax = vax + j_ima * jx; vay = vay + j_ima * jy;
+            wa = wa + j_iia * (j_rax * jy - j_ray * jx);
+            vbx = vbx + j_imb * (-jx); vby = vby + j_imb * (-jy);
+            wb = wb + j_iib * (j_rbx * (-jy) - j_rby * (-jx));
+            j_accx = j_accx + jx; j_accy = j_accy + jy;
+            E[L.vel_x + ja] = vax; E[L.vel_y + ja] = vay; E[L.omega + ja] = wa;
+            E[L.vel_x + jb] = vbx; E[L.vel_y + jb] = vby; E[L.omega + jb] = wb;
+          }
+          __syncthreads();
+        }
+        for_each_round(env_rounds, my_rounds, [&](int r) {
+          int idx = table[r * G + k];
+          float* rp = idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW;
+          PairRec rc;
+          rec_load(rp, rc);
+          S::solve_pair(E, rc);
+#pragma unroll
+          for (int q = 0; q < 2; ++q) { rp[5 + 10 * q + 8] = rc.lam_n[q]; rp[5 + 10 * q + 9] = rc.lam_t[q]; }
+        });
+      }
+
+      // ---- Euler step of position and rotation (Alg. 1) ----
+      for (int i = k; i < N; i += G) {
+        if (f2i(E[L.shape_flags + i]) & 1) {
+          E[L.pos_x + i] = E[L.pos_x + i] + h * E[L.vel_x + i];
+          E[L.pos_y + i] = E[L.pos_y + i] + h * E[L.vel_y + i];
+          float th = E[L.theta + i] + h * E[L.omega + i];
+          E[L.theta + i] = th;
+          float sn, cs;
+          sincosf(th, &sn, &cs);
+          E[K::X_COS + i] = cs;
+          E[K::X_SIN + i] = sn;
+        }
+      }
+      __syncthreads();
+
+      // ---- positional corrections (A.3.7, A.4.1); the pair's accumulated impulses go to HBM ----
+      for_each_round(env_rounds, my_rounds, [&](int r) {
+        int idx = table[r * G + k];
+        const float* rp = idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW;
+        const float nx = rp[0], ny = rp[1], corr = rp[3];
+        const int ab = f2i(rp[4]);
+        const int a = ab & 0xff, b = (ab >> 8) & 0xff;
+        const float ima = E[L.inv_mass + a], imb = E[L.inv_mass + b];
+        E[L.pos_x + a] = E[L.pos_x + a] - (ima * corr) * nx;
+        E[L.pos_y + a] = E[L.pos_y + a] - (ima * corr) * ny;
+        E[L.pos_x + b] = E[L.pos_x + b] + (imb * corr) * nx;
+        E[L.pos_y + b] = E[L.pos_y + b] + (imb * corr) * ny;
+        if (env_ok)
+          *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(a, b)) =
+              make_float4(rp[13], rp[14], rp[23], rp[24]);
+      });
+      for (int lv = 0; lv < wave_levels; ++lv) {
+        if (k < J && j_live && j_level == lv) {
+          float ca = E[K::X_COS + ja], sa = E[K::X_SIN + ja], cb = E[K::X_COS + jb], sb = E[K::X_SIN + jb];
+          float xax = E[L.pos_x + ja] + (ca * j_aax - sa * j_aay), xay = E[L.pos_y + ja] + (sa * j_aax + ca * j_aay);
+          float xbx = E[L.pos_x + jb] + (cb * j_abx - sb * j_aby), xby = E[L.pos_y + jb] + (sb * j_abx + cb * j_aby);
+          float cf = prm.joint_beta / (j_ima + j_imb);
+          float cx = cf * (xax - xbx), cy = cf * (xay - xby);
+          E[L.pos_x + ja] = E[L.pos_x + ja] - j_ima * cx;
+          E[L.pos_y + ja] = E[L.pos_y + ja] - j_ima * cy;
+          E[L.pos_x + jb] = E[L.pos_x + jb] + j_imb * cx;
+          E[L.pos_y + jb] = E[L.pos_y + jb] + j_imb * cy;
+        }
+        __syncthreads();
+      }
+    }
+  }
+
+  // ---- write back: dynamic shape state, joint accumulators, pair states ----
+  if (k < J) {
+    E[L.acc_x + k] = j_accx;
+    E[L.acc_y + k] = j_accy;
+    E[L.acc_ang + k] = j_acca;
+  }
+  __syncthreads();
+  for (int e = 0; e < K::EPW; ++e) {
+    if (env0 + e < n_envs) {
+      const float* src = lds + e * K::LDS_STRIDE;
+      float* dst = state + (size_t)(env0 + e) * K::REC_WORDS;
+      for (int w = lane; w < 6 * N; w += 64) dst[w] = src[w];
+      for (int w = lane; w < 3 * J; w += 64) dst[L.acc_x + w] = src[L.acc_x + w];
+    }
+  }
+  if (env_ok) {
+    unsigned char* ps = reinterpret_cast<unsigned char*>(Rg + L.pair_state);
+    for (int r = 0; r < R; ++r) {
+      int a, b;
+      if (S::sched_pair(r, k, a, b)) ps[S::pair_index(a, b)] = (unsigned char)((prev_bits >> (2 * r)) & 3u);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Small data-movement kernels
+// ---------------------------------------------------------------------------------------------------
+// Scene records -> state records (k2d_reset); zeroes the accumulators and the pair states.
+__global__ void k2d_reset_kernel(float* state, const float* scenes, const int32_t* ids, int n, int n_envs,
+                                 int rec_words, k2d_layout L) {
+  int r = blockIdx.x;
+  if (r >= n) return;
+  int env = ids ? ids[r] : r;
+  if (env < 0 || env >= n_envs) return;
+  float* dst = state + (size_t)env * rec_words;
+  const float* src = scenes + (size_t)r * L.scene_words;
+  for (int w = threadIdx.x; w < L.state_words; w += blockDim.x) {
+    float v = 0.f;
+    if (w < L.scene_words) {
+      v = src[w];
+      if (w >= L.acc_x && w < L.thr_flags) v = 0.f;   // acc_x, acc_y, acc_ang are contiguous
+    }
+    dst[w] = v;
+  }
+}
+
+// Full records out of (dir = 0) or into (dir = 1) the batch.
+__global__ void k2d_copy_state_kernel(float* state, float* records, int n_envs, int rec_words, k2d_layout L,
+                                      int dir) {
+  const int state_words = L.state_words;
+  int env = blockIdx.x;
+  if (env >= n_envs) return;
+  float* a = state + (size_t)env * rec_words;
+  float* b = records + (size_t)env * state_words;
+  const unsigned char* ps = reinterpret_cast<const unsigned char*>(a + L.pair_state);
+  for (int w = threadIdx.x; w < state_words; w += blockDim.x) {
+    if (dir == 0) {
+      float v = a[w];
+      // accumulated impulses of manifold points that are not in collision are zero by definition (A.7)
+      if (w >= L.lambda && w < L.lambda + 4 * L.n_pairs) {
+        int q = w - L.lambda;
+        if (!((ps[q >> 2] >> ((q >> 1) & 1)) & 1)) v = 0.f;
+      }
+      b[w] = v;
+    } else {
+      a[w] = b[w];
+    }
+  }
+}
+
+// Flat symbolic observation (Tables 5-7): one thread per entity.
+__global__ void k2d_obs_kernel(const float* state, float* obs, int n_envs, int rec_words, k2d_layout L, int P, int C,
+                               int J, int T) {
+  const int n_ent = P + C + J + T;
+  long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long)n_envs * n_ent) return;
+  int env = (int)(gid / n_ent), ent = (int)(gid % n_ent);
+  const float* S = state + (size_t)env * rec_words;
+  float* o = obs + (size_t)env * L.obs_dim;
+  if (ent < P + C) {
+    int i = ent;
+    o += (i < P) ? i * 23 : P * 23 + (i - P) * 15;
+    int fl = __float_as_int(S[L.shape_flags + i]);
+    float sn, cs;
+    sincosf(S[L.theta + i], &sn, &cs);
+    o[0] = S[L.pos_x + i]; o[1] = S[L.pos_y + i]; o[2] = S[L.vel_x + i]; o[3] = S[L.vel_y + i];
+    o[4] = S[L.inv_mass + i]; o[5] = S[L.inv_inertia + i]; o[6] = S[L.density + i];
+    o[7] = tanhf(S[L.omega + i] / 10.f);
+    o[8] = sn; o[9] = cs; o[10] = S[L.friction + i]; o[11] = S[L.restitution + i];
+    int q = 12;
+    if (i < P) {
+      for (int v = 0; v < 8; ++v) o[q++] = S[L.verts + v * P + i];
+      o[q++] = (float)__float_as_int(S[L.n_verts + i]);
+    } else {
+      o[q++] = S[L.radius + (i - P)];
+    }
+    o[q++] = (float)(fl & 1);
+    o[q++] = (float)(fl >> 8);
+  } else if (ent < P + C + J) {
+    int j = ent - P - C;
+    o += P * 23 + C * 15 + j * 11;
+    int fl = __float_as_int(S[L.joint_flags + j]);
+    int a = __float_as_int(S[L.joint_a + j]), b = __float_as_int(S[L.joint_b + j]);
+    a = min(max(a, 0), P + C - 1); b = min(max(b, 0), P + C - 1);
+    float sn, cs;
+    sincosf(S[L.theta + a] - S[L.theta + b], &sn, &cs);
+    o[0] = (float)(fl & 1); o[1] = (float)((fl >> 1) & 1);
+    o[2] = S[L.anchor_a_x + j]; o[3] = S[L.anchor_a_y + j]; o[4] = S[L.anchor_b_x + j]; o[5] = S[L.anchor_b_y + j];
+    o[6] = S[L.motor_power + j]; o[7] = S[L.motor_speed + j]; o[8] = (float)((fl >> 2) & 1);
+    o[9] = sn; o[10] = cs;
+  } else {
+    int t = ent - P - C - J;
+    o += P * 23 + C * 15 + J * 11 + t * 6;
+    int fl = __float_as_int(S[L.thr_flags + t]);
+    float sn, cs;
+    sincosf(S[L.thr_angle + t], &sn, &cs);
+    o[0] = (float)(fl & 1); o[1] = S[L.thr_pos_x + t]; o[2] = S[L.thr_pos_y + t]; o[3] = S[L.thr_power + t];
+    o[4] = sn; o[5] = cs;
+  }
+}
+
+// Active manifold points per pair and the shape adjacency words, from the pair-state bytes.
+__global__ void k2d_contacts_kernel(const float* state, uint8_t* pair_count, uint32_t* shape_adj, int n_envs,
+                                    int rec_words, k2d_layout L) {
+  int env = blockIdx.x;
+  if (env >= n_envs) return;
+  const unsigned char* ps = reinterpret_cast<const unsigned char*>(state + (size_t)env * rec_words + L.pair_state);
+  const int N = L.n_shapes;
+  if (pair_count)
+    for (int p = threadIdx.x; p < L.n_pairs; p += blockDim.x)
+      pair_count[(size_t)env * L.n_pairs + p] = (uint8_t)((ps[p] & 1) + ((ps[p] >> 1) & 1));
+  if (shape_adj)
+    for (int i = threadIdx.x; i < N; i += blockDim.x) {
+      uint32_t w = 0;
+      for (int j = 0; j < N; ++j) {
+        if (j == i) continue;
+        int a = min(i, j), b = max(i, j);
+        if (ps[a * (2 * N - a - 1) / 2 + (b - a - 1)] & 3) w |= 1u << j;
+      }
+      shape_adj[(size_t)env * N + i] = w;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------------------------------
+using CfgS = Cfg<5, 2, 1, 1, 21>;
+using CfgM = Cfg<6, 3, 2, 2, 36>;
+using CfgL = Cfg<12, 4, 6, 2, 20>;
+
+int caps_class(const k2d_caps* c) {
+  if (!c) return -1;
+  if (c->n_polygons == 5 && c->n_circles == 2 && c->n_joints == 1 && c->n_thrusters == 1) return 0;
+  if (c->n_polygons == 6 && c->n_circles == 3 && c->n_joints == 2 && c->n_thrusters == 2) return 1;
+  if (c->n_polygons == 12 && c->n_circles == 4 && c->n_joints == 6 && c->n_thrusters == 2) return 2;
+  return -1;
+}
+int rec_words_of(int cls) { return cls == 0 ? CfgS::REC_WORDS : cls == 1 ? CfgM::REC_WORDS : CfgL::REC_WORDS; }
+
+template <class K>
+int launch_step(float* state, const float* actions, int n_envs, int n_steps, const Params& prm, hipStream_t st) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k2d_step_kernel<K>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, K::LDS_BYTES) != hipSuccess)
+      return K2D_E_HIP;
+    attr_done = true;
+  }
+  int grid = (n_envs + K::EPW - 1) / K::EPW;
+  hipLaunchKernelGGL(k2d_step_kernel<K>, dim3(grid), dim3(64), K::LDS_BYTES, st, state, actions, n_envs, n_steps, prm);
+  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+}
+
+}  // namespace
+
+struct k2d_batch {
+  int cls;
+  k2d_caps caps;
+  k2d_params params;
+  k2d_layout layout;
+  int n_envs;
+  int rec_words;
+  float* state;
+};
+
+extern "C" {
+
+int k2d_get_layout(const k2d_caps* caps, k2d_layout* out) {
+  if (!caps || !out) return K2D_E_ARG;
+  if (caps_class(caps) < 0) return K2D_E_CAP;
+  *out = make_layout(caps->n_polygons, caps->n_circles, caps->n_joints, caps->n_thrusters);
+  return K2D_OK;
+}
+
+size_t k2d_state_bytes(const k2d_caps* caps, int n_envs) {
+  int cls = caps_class(caps);
+  if (cls < 0 || n_envs < 1) return 0;
+  return (size_t)n_envs * rec_words_of(cls) * sizeof(float);
+}
+
+int k2d_alloc_batch(const k2d_caps* caps, const k2d_params* params, int n_envs, void* state_dev, size_t state_bytes,
+                    k2d_batch** out) {
+  if (!caps || !params || !state_dev || !out || n_envs < 1) return K2D_E_ARG;
+  if ((reinterpret_cast<uintptr_t>(state_dev) & 255u) != 0) return K2D_E_ARG;
+  int cls = caps_class(caps);
+  if (cls < 0) return K2D_E_CAP;
+  if (params->n_substeps < 1 || params->n_iters < 0 || !(params->dt > 0.f)) return K2D_E_ARG;
+  if (state_bytes < k2d_state_bytes(caps, n_envs)) return K2D_E_SIZE;
+  k2d_batch* b = new (std::nothrow) k2d_batch;
+  if (!b) return K2D_E_ARG;
+  b->cls = cls;
+  b->caps = *caps;
+  b->params = *params;
+  b->layout = make_layout(caps->n_polygons, caps->n_circles, caps->n_joints, caps->n_thrusters);
+  b->n_envs = n_envs;
+  b->rec_words = rec_words_of(cls);
+  b->state = static_cast<float*>(state_dev);
+  *out = b;
+  return K2D_OK;
+}
+
+int k2d_free_batch(k2d_batch* batch) {
+  delete batch;
+  return K2D_OK;
+}
+
+int k2d_reset(k2d_batch* b, const void* scenes_dev, const int32_t* env_ids_dev, int n, void* stream) {
+  if (!b || !scenes_dev || n < 1) return K2D_E_ARG;
+  if (!env_ids_dev && n > b->n_envs) return K2D_E_SIZE;
+  hipLaunchKernelGGL(k2d_reset_kernel, dim3(n), dim3(256), 0, static_cast<hipStream_t>(stream), b->state,
+                     static_cast<const float*>(scenes_dev), env_ids_dev, n, b->n_envs, b->rec_words, b->layout);
+  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+}
+
+int k2d_step(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, void* stream) {
+  if (!b || !actions_dev || n_steps < 1) return K2D_E_ARG;
+  if (n_envs != b->n_envs) return K2D_E_SIZE;
+  const k2d_params& p = b->params;
+  Params prm;
+  prm.h = p.dt / (float)p.n_substeps;
+  prm.gravity_y = p.gravity_y;
+  prm.n_substeps = p.n_substeps;
+  prm.n_iters = p.n_iters;
+  prm.warm_start = p.warm_start;
+  prm.alpha = p.alpha; prm.beta = p.beta; prm.gamma = p.gamma; prm.rho = p.rho; prm.slop = p.slop;
+  prm.rest_thr = p.restitution_threshold;
+  prm.clip_thr = p.clip_thruster_01;
+  prm.joint_alpha = p.joint_alpha; prm.joint_beta = p.joint_beta; prm.tie_eps = p.tie_eps;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  switch (b->cls) {
+    case 0: return launch_step<CfgS>(b->state, actions_dev, n_envs, n_steps, prm, st);
+    case 1: return launch_step<CfgM>(b->state, actions_dev, n_envs, n_steps, prm, st);
+    default: return launch_step<CfgL>(b->state, actions_dev, n_envs, n_steps, prm, st);
+  }
+}
+
+int k2d_read_obs(k2d_batch* b, float* obs_dev, void* stream) {
+  if (!b || !obs_dev) return K2D_E_ARG;
+  const k2d_caps& c = b->caps;
+  long n = (long)b->n_envs * (c.n_polygons + c.n_circles + c.n_joints + c.n_thrusters);
+  hipLaunchKernelGGL(k2d_obs_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     b->state, obs_dev, b->n_envs, b->rec_words, b->layout, c.n_polygons, c.n_circles, c.n_joints,
+                     c.n_thrusters);
+  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+}
+
+int k2d_read_contacts(k2d_batch* b, uint8_t* pair_count_dev, uint32_t* shape_adj_dev, void* stream) {
+  if (!b) return K2D_E_ARG;
+  if (!pair_count_dev && !shape_adj_dev) return K2D_OK;
+  hipLaunchKernelGGL(k2d_contacts_kernel, dim3(b->n_envs), dim3(128), 0, static_cast<hipStream_t>(stream), b->state,
+                     pair_count_dev, shape_adj_dev, b->n_envs, b->rec_words, b->layout);
+  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+}
+
+int k2d_read_state(k2d_batch* b, void* records_dev, void* stream) {
+  if (!b || !records_dev) return K2D_E_ARG;
+  hipLaunchKernelGGL(k2d_copy_state_kernel, dim3(b->n_envs), dim3(256), 0, static_cast<hipStream_t>(stream), b->state,
+                     static_cast<float*>(records_dev), b->n_envs, b->rec_words, b->layout, 0);
+  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+}
+
+int k2d_write_state(k2d_batch* b, const void* records_dev, void* stream) {
+  if (!b || !records_dev) return K2D_E_ARG;
+  hipLaunchKernelGGL(k2d_copy_state_kernel, dim3(b->n_envs), dim3(256), 0, static_cast<hipStream_t>(stream), b->state,
+                     const_cast<float*>(static_cast<const float*>(records_dev)), b->n_envs, b->rec_words,
+                     b->layout, 1);
+  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+}
+
+}  // extern "C"
