@@ -130,6 +130,46 @@ struct Params {   // device copy of k2d_params with the substep precomputed
 };
 
 __device__ __forceinline__ int f2i(float f) { return __float_as_int(f); }
+
+// sin, cos and tanh as fixed sequences of IEEE fp32 operations (no maths-library call, no fused
+// multiply-add): quadrant reduction against a three-term split of pi/2, then polynomials in r*r; tanh
+// by polynomial below 0.55 and through e^{2|x|} above.  Any implementation that performs the same
+// operations in the same order produces the same bits, which is what lets a CPU run of the same step be
+// compared with this one exactly.  Absolute error below 1.5e-7.
+__device__ __forceinline__ void k2d_sincos(float x, float& sn, float& cs) {
+  const float q = rintf(x * 0x1.45f306p-1f);
+  float r = x - q * 0x1.92p+0f;
+  r = r - q * 0x1.fb4p-12f;
+  r = r - q * 0x1.4442d2p-24f;
+  const float z = r * r;
+  const float s = r + (r * z) * ((-0x1.9b021cp-13f * z + 0x1.110ccap-7f) * z + -0x1.555554p-3f);
+  const float c = (1.0f - 0.5f * z) + (z * z) * ((0x1.9c05c8p-16f * z + -0x1.6c1354p-10f) * z + 0x1.555554p-5f);
+  const int quad = (int)q & 3;
+  const float a = (quad & 1) ? c : s;      // value that lands in the sine slot before the sign
+  const float b = (quad & 1) ? s : c;
+  sn = (quad & 2) ? -a : a;
+  cs = ((quad + 1) & 2) ? -b : b;
+}
+__device__ __forceinline__ float k2d_tanh(float x) {
+  const float a = fabsf(x);
+  float y;
+  if (a < 0.55f) {
+    const float z = a * a;
+    y = a + (a * z) * ((((-0x1.b3b502p-8f * z + 0x1.5d873cp-6f) * z + -0x1.b9aa82p-5f) * z + 0x1.111018p-3f) * z +
+                       -0x1.555554p-2f);
+  } else {
+    const float t2 = 2.0f * a;
+    const float t = (t2 < 40.0f) ? t2 : 40.0f;
+    const float n = rintf(t * 0x1.715476p+0f);
+    float r = t - n * 0x1.62cp-1f;
+    r = r - n * 0x1.217f7ep-12f;
+    float e = (1.0f + r) + (r * r) * ((((0x1.6d435ap-10f * r + 0x1.120b66p-7f) * r + 0x1.5554e8p-5f) * r +
+                                       0x1.5554dcp-3f) * r + 0.5f);
+    e = ldexpf(e, (int)n);
+    y = 1.0f - 2.0f / (e + 1.0f);
+  }
+  return x < 0.0f ? -y : y;
+}
 __device__ __forceinline__ float i2f(int i) { return __int_as_float(i); }
 
 // One active pair of the current substep.  Body indices and per-point activity are packed in `ab`.
@@ -445,7 +485,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
   // ---- per-launch derived data ----
   for (int i = k; i < N; i += G) {
     float sn, cs;
-    sincosf(E[L.theta + i], &sn, &cs);
+    k2d_sincos(E[L.theta + i], sn, cs);
     E[K::X_COS + i] = cs;
     E[K::X_SIN + i] = sn;
     float br;
@@ -524,7 +564,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
     if (!idx_ok) t_body = 0;
     t_live = (fl & 1) && idx_ok && (f2i(E[L.shape_flags + t_body]) & 1);
     t_px = E[L.thr_pos_x + k]; t_py = E[L.thr_pos_y + k];
-    sincosf(E[L.thr_angle + k], &t_dy, &t_dx);
+    k2d_sincos(E[L.thr_angle + k], t_dy, t_dx);
     t_power = E[L.thr_power + k];
   }
   // pairs: lane k owns pair k of every round; eligibility is fixed for the launch
@@ -609,7 +649,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         j_angb = prm.gamma * (E[L.theta + ja] - E[L.theta + jb] - j_thf);
         if (!j_fixed && j_motor) {   // A.5
           float arg = (E[L.omega + ja] - E[L.omega + jb] - j_speed * act_m) * prm.rho;
-          motor = j_power * tanhf(arg) * h;
+          motor = j_power * k2d_tanh(arg) * h;
         }
       }
       float t_ix = 0.f, t_iy = 0.f, t_rx = 0.f, t_ry = 0.f;
@@ -792,7 +832,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           float th = E[L.theta + i] + h * E[L.omega + i];
           E[L.theta + i] = th;
           float sn, cs;
-          sincosf(th, &sn, &cs);
+          k2d_sincos(th, sn, cs);
           E[K::X_COS + i] = cs;
           E[K::X_SIN + i] = sn;
         }
@@ -916,10 +956,10 @@ __global__ void k2d_obs_kernel(const float* state, float* obs, int n_envs, int r
     o += (i < P) ? i * 23 : P * 23 + (i - P) * 15;
     int fl = __float_as_int(S[L.shape_flags + i]);
     float sn, cs;
-    sincosf(S[L.theta + i], &sn, &cs);
+    k2d_sincos(S[L.theta + i], sn, cs);
     o[0] = S[L.pos_x + i]; o[1] = S[L.pos_y + i]; o[2] = S[L.vel_x + i]; o[3] = S[L.vel_y + i];
     o[4] = S[L.inv_mass + i]; o[5] = S[L.inv_inertia + i]; o[6] = S[L.density + i];
-    o[7] = tanhf(S[L.omega + i] / 10.f);
+    o[7] = k2d_tanh(S[L.omega + i] / 10.f);
     o[8] = sn; o[9] = cs; o[10] = S[L.friction + i]; o[11] = S[L.restitution + i];
     int q = 12;
     if (i < P) {
@@ -937,7 +977,7 @@ __global__ void k2d_obs_kernel(const float* state, float* obs, int n_envs, int r
     int a = __float_as_int(S[L.joint_a + j]), b = __float_as_int(S[L.joint_b + j]);
     a = min(max(a, 0), P + C - 1); b = min(max(b, 0), P + C - 1);
     float sn, cs;
-    sincosf(S[L.theta + a] - S[L.theta + b], &sn, &cs);
+    k2d_sincos(S[L.theta + a] - S[L.theta + b], sn, cs);
     o[0] = (float)(fl & 1); o[1] = (float)((fl >> 1) & 1);
     o[2] = S[L.anchor_a_x + j]; o[3] = S[L.anchor_a_y + j]; o[4] = S[L.anchor_b_x + j]; o[5] = S[L.anchor_b_y + j];
     o[6] = S[L.motor_power + j]; o[7] = S[L.motor_speed + j]; o[8] = (float)((fl >> 2) & 1);
@@ -947,7 +987,7 @@ __global__ void k2d_obs_kernel(const float* state, float* obs, int n_envs, int r
     o += P * 23 + C * 15 + J * 11 + t * 6;
     int fl = __float_as_int(S[L.thr_flags + t]);
     float sn, cs;
-    sincosf(S[L.thr_angle + t], &sn, &cs);
+    k2d_sincos(S[L.thr_angle + t], sn, cs);
     o[0] = (float)(fl & 1); o[1] = S[L.thr_pos_x + t]; o[2] = S[L.thr_pos_y + t]; o[3] = S[L.thr_power + t];
     o[4] = sn; o[5] = cs;
   }
