@@ -1,0 +1,144 @@
+#!/usr/bin/env python3
+"""Throughput of the batched 2D rigid-body step on one MI355X.
+
+One "step" of this benchmark is one pass of the whole hot path over one batch: `k2d_step` advancing every
+environment of the workload by its full number of engine steps (config "L": 8192 environments x 256
+steps, 3 substeps x 10 solver sweeps), starting from the freshly reset synthetic scenes.  Inputs (scenes,
+actions) are resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..4] [--cpu-envs N] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+FP32_VALU_PEAK_TFLOPS = 157.3   # MI355X vector fp32: 256 CU x 4 SIMD x 16 lanes x 2 (packed) x 2 (fma) x 2.4 GHz
+
+
+def read_traffic(name):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (None if not collected)."""
+    path = os.path.join(ROOT, "profiles", "k2d_step_%s_hbm_traffic.txt" % name)
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch="):
+                    return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2, help="workload 0..4 (default 2 = L, 8192 envs x 256 steps)")
+    ap.add_argument("--cpu-envs", type=int, default=2048, help="environments of the CPU-oracle sample")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg (flop model then uses "
+                    "a 256-environment oracle run only for the contact statistics)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (environments are independent; more GPUs would each take "
+              "a slice of the environment axis with no exchange); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import scenegen
+    import paper_2410_23208_amd as k2d
+    from paper_2410_23208_amd import workmodel
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    cfg = scenegen.CONFIGS[args.config]
+    n_envs, n_steps = cfg["n_envs"], cfg["n_steps"]
+    caps, params, scene = scenegen.make_scene(args.config)
+    actions_h = scenegen.make_actions(args.config, n_steps, n_envs)
+    dev = torch.device("cuda:0")
+    words = torch.from_numpy(k2d.pack_scenes(caps, scene).view(np.int32)).to(dev)
+    actions = torch.from_numpy(actions_h).to(dev)
+    batch = k2d.Batch(caps, n_envs, params)
+    torch.cuda.synchronize()
+
+    def one_pass(ev=None):
+        batch.reset(words)
+        if ev:
+            ev[0].record()
+        batch.step(actions, n_steps)
+        if ev:
+            ev[1].record()
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_pass(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = [a.elapsed_time(b) for a, b in events]
+    env_steps = n_envs * n_steps
+    value = args.steps * env_steps / wall
+
+    # ---- CPU oracle on a bounded sample of the same workload: baseline + contact statistics ----
+    from oracle.k2d_oracle import Oracle
+    cores = min(len(os.sched_getaffinity(0)), 16)
+    ns = min(n_envs, 256 if args.no_cpu else args.cpu_envs)
+    sub = scenegen.select_envs(scene, np.arange(ns))
+    ora = Oracle(caps, ns, params, "f32")
+    ora.load_scene(sub)
+    t1 = time.perf_counter()
+    ora.step(actions_h[:, :ns], n_threads=cores)
+    cpu_t = time.perf_counter() - t1
+    nsub = ora.get("substeps_done").sum()
+    slots = ora.get("active_slots_sum").sum() / nsub
+    pairs = ora.get("active_pairs_sum").sum() / nsub
+    ppov = ora.get("pp_overlap_sum").sum() / nsub
+    flops_step, st = workmodel.flops_per_env_step(caps, scene, params, slots, pairs, ppov)
+
+    # spot check of the timed path against the oracle (same launch configuration, sampled environments)
+    gs = k2d.unpack_state(caps, batch.read_state()[:ns].cpu().numpy())
+    os_ = ora.state()
+    parity_ok = all(np.array_equal(gs[k], os_[k]) for k in ("pos", "theta", "vel", "omega", "pair_count"))
+
+    kern_avg = float(np.mean(kern_ms)) * 1e-3
+    achieved = flops_step * env_steps / kern_avg / 1e12
+    out = {
+        "metric": "physics env-steps/sec on 1 MI355X (%s scenes, %d envs)" % (cfg["name"], n_envs),
+        "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config %d: %s, %d envs x %d steps, %d substeps x %d solver sweeps, caps P/C/J/T=%s"
+                   % (args.config, cfg["name"], n_envs, n_steps, params["n_substeps"], params["n_iters"],
+                      "/".join(map(str, caps))),
+                   "env_steps_per_launch": env_steps, "seed": scenegen.SEED},
+        "roofline": {"bound": "alu", "achieved": achieved, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / FP32_VALU_PEAK_TFLOPS, "traffic": read_traffic(cfg["name"]),
+                     "kernel": "k2d_step_kernel", "kernel_ms_avg": kern_avg * 1e3, "kernel_ms": kern_ms,
+                     "flops_per_env_step": flops_step, "active_points_per_substep": float(slots),
+                     "active_pairs_per_substep": float(pairs), "eligible_pairs": st["n_eligible"],
+                     "hbm_GBps_algorithmic": (2 * 4 * k2d.get_layout(caps)["state_words"] * n_envs
+                                              + 4 * actions.numel()) / kern_avg / 1e9},
+        "cpu_baseline": {"value": ns * n_steps / cpu_t, "unit": "env-steps/s", "cores": cores, "kind": "oracle",
+                         "sample": "first %d of %d environments, all %d steps, fp32 oracle, %d threads, %.1f s"
+                                   % (ns, n_envs, n_steps, cores, cpu_t)},
+        "parity_spot_check": "bit-identical to the oracle on %d sampled environments" % ns if parity_ok
+                             else "MISMATCH against the oracle on the sampled environments",
+    }
+    print(json.dumps(out))
+    if not parity_ok:
+        sys.exit(1)
+
+
+if __name__ == "__main__":
+    main()

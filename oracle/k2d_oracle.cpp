@@ -175,6 +175,7 @@ struct Manifold {
   R pen[2] = {0, 0};
   int valid[2] = {0, 0};
   int active[2] = {0, 0};
+  int overlap = 0;          // polygon pairs: no separating axis was found (work counter only)
   double margin = std::numeric_limits<double>::infinity();  // distance of the nearest discrete decision
 };
 
@@ -193,7 +194,10 @@ struct Env {
   std::vector<Manifold<R>> manifolds;  // lexicographic pair order
   std::vector<ContactAcc<R>> acc;      // lexicographic pair order
   double min_margin = std::numeric_limits<double>::infinity();
-  int n_active_slots_sum = 0;          // sum over substeps of active manifold points (for the flop model)
+  // work counters, summed over substeps (they feed the benchmark's count of arithmetic, nothing else)
+  int n_active_slots_sum = 0;          // active manifold points
+  int n_active_pairs_sum = 0;          // pairs with at least one active point
+  int n_pp_overlap_sum = 0;            // polygon pairs that went past the separating-axis test
   int n_substeps_done = 0;
 };
 
@@ -335,6 +339,7 @@ void manifold_pp(const WorldPoly<R>& A, const WorldPoly<R>& B, R tie_eps, Manifo
   face_query(B, A, sb, ib, sb2);
   note(m.margin, std::max(sa, sb));
   if (std::max(sa, sb) >= R(0)) return;  // a separating axis exists: no collision
+  m.overlap = 1;
   bool ref_b = sb > sa + tie_eps;
   note(m.margin, double(sb) - (double(sa) + double(tie_eps)));
   note(m.margin, ref_b ? double(sb) - double(sb2) : double(sa) - double(sa2));
@@ -500,6 +505,8 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
         else manifold_cc(a.pos, a.radius, b.pos, b.radius, m);
         for (int k = 0; k < 2; ++k) m.active[k] = m.valid[k] && m.pen[k] > R(0);
         E.min_margin = std::min(E.min_margin, m.margin);
+        E.n_pp_overlap_sum += m.overlap;
+        E.n_active_pairs_sum += (m.active[0] || m.active[1]);
       }
       E.manifolds[pair_index(i, j, N)] = m;
     }
@@ -796,6 +803,8 @@ struct Batch : BatchBase {
     FIELD("pair_margin", NP, e.manifolds[i].margin, double)
     FIELD("min_margin", 1, e.min_margin, double)
     FIELD("active_slots_sum", 1, e.n_active_slots_sum, II)
+    FIELD("active_pairs_sum", 1, e.n_active_pairs_sum, II)
+    FIELD("pp_overlap_sum", 1, e.n_pp_overlap_sum, II)
     FIELD("substeps_done", 1, e.n_substeps_done, II)
 #undef FIELD
 #undef RR

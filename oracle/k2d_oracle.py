@@ -138,6 +138,8 @@ class Oracle:
                 self.set(f, scene[f], env_ids)
             else:
                 self.set(f, np.zeros((rows, self.field_size(f))), env_ids)
+        # a fresh episode has had no substep yet: no collisions to report
+        self.set("pair_active", np.zeros((rows, self.field_size("pair_active"))), env_ids)
 
     def step(self, actions, n_steps=None, n_threads=1):
         """actions: [n_steps, n_envs, J+T]."""

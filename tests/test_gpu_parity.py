@@ -1,0 +1,228 @@
+"""GPU parity tests: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: integer outputs (active-contact masks, manifold point counts) bit-exact; floating-point state within
+1e-4 absolute + 1e-4 relative after one step and 1e-3 after 16 steps, environments whose nearest discrete
+decision came within 1e-5 of its threshold compared separately.  The kernel is built without contraction
+and with the same fixed-sequence sin/cos/tanh as the oracle, so the stronger statement -- identical bits --
+is asserted too.
+"""
+import numpy as np
+import pytest
+
+import scenegen
+import parity
+from helpers import SceneBuilder, params as mkparams
+
+pytestmark = pytest.mark.gpu
+
+SMALL = {0: 67, 1: 131, 2: 259, 3: 131, 4: 195}     # several wavefronts and a ragged tail each
+
+
+def _both(cfg, n, steps, chunk=None):
+    caps, prm, sc = scenegen.make_scene(cfg, n_envs=n)
+    act = scenegen.make_actions(cfg, steps, n)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b = parity.run_gpu(caps, prm, sc, act, chunk=chunk)
+    return b, o, caps
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
+def test_one_step_within_1e4(cfg):
+    b, o, _ = _both(cfg, SMALL[cfg], 1)
+    res = parity.compare(b.state_dict(), o.state(), atol=1e-4, rtol=1e-4)
+    parity.assert_parity(res, "config %d, 1 step" % cfg, min_clean_frac=0.9)
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
+def test_sixteen_steps_within_1e3(cfg):
+    b, o, _ = _both(cfg, SMALL[cfg], 16)
+    res = parity.compare(b.state_dict(), o.state(), atol=1e-3, rtol=1e-3)
+    parity.assert_parity(res, "config %d, 16 steps" % cfg, min_clean_frac=0.6)
+    assert len(res["bad_flagged"]) == 0      # even near-threshold environments agree in practice
+
+
+@pytest.mark.parametrize("cfg,steps", [(0, 200), (1, 64), (2, 64), (3, 96), (4, 64)])
+def test_bit_identical_rollouts(cfg, steps):
+    b, o, _ = _both(cfg, SMALL[cfg], steps)
+    gs, os_ = b.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    assert (os_["pair_count"] > 0).sum() > 0
+
+
+def test_contacts_and_observation_outputs():
+    b, o, caps = _both(3, 131, 40)
+    pc, adj = b.read_contacts()
+    assert np.array_equal(pc.cpu().numpy().astype(np.float64), o.get("pair_count"))
+    assert np.array_equal(adj.cpu().numpy().astype(np.int64) & 0xFFFFFFFF, o.get("shape_adj").astype(np.int64))
+    assert pc.sum().item() > 100
+    obs = b.read_obs().cpu().numpy().astype(np.float64)
+    ref = o.obs()
+    assert obs.shape == ref.shape
+    assert np.array_equal(obs, ref)
+
+
+def test_chunking_and_determinism():
+    """n_steps in one launch == the same steps in launches of 1, 3, ...; a rerun gives identical bytes."""
+    caps, prm, sc = scenegen.make_scene(2, n_envs=100)
+    act = scenegen.make_actions(2, 12, 100)
+    recs = []
+    for chunk in (12, 1, 3, 12):
+        b = parity.run_gpu(caps, prm, sc, act, chunk=chunk)
+        recs.append(b.read_state().cpu().numpy())
+    for r in recs[1:]:
+        assert np.array_equal(recs[0], r)
+
+
+def test_state_roundtrip_checkpoint_resume():
+    import torch
+    import paper_2410_23208_amd as k2d
+    caps, prm, sc = scenegen.make_scene(3, n_envs=64)
+    act = torch.from_numpy(scenegen.make_actions(3, 30, 64)).cuda()
+    a = k2d.Batch(caps, 64, prm)
+    a.reset(k2d.pack_scenes(caps, sc))
+    a.step(act[:20].contiguous())
+    snap = a.read_state()
+    a.step(act[20:].contiguous())
+    b = k2d.Batch(caps, 64, prm)
+    b.write_state(snap)
+    b.step(act[20:].contiguous())
+    assert torch.equal(a.read_state(), b.read_state())
+
+
+def test_heterogeneous_batch_with_resets():
+    """Config 4 protocol: one step, then a seeded 5 % of the environments restart from new scenes."""
+    import torch
+    import paper_2410_23208_amd as k2d
+    from oracle.k2d_oracle import Oracle
+    n, steps = 195, 24
+    caps, prm, sc = scenegen.make_scene(4, n_envs=n)
+    act = scenegen.make_actions(4, steps, n)
+    o = Oracle(caps, n, prm, "f32")
+    o.load_scene(sc)
+    b = k2d.Batch(caps, n, prm)
+    b.reset(k2d.pack_scenes(caps, sc))
+    act_d = torch.from_numpy(act).cuda()
+    n_reset = 0
+    for s in range(steps):
+        o.step(act[s:s + 1])
+        b.step(act_d[s:s + 1].contiguous())
+        ids = scenegen.reset_ids(4, s, n)
+        if len(ids):
+            _, _, fresh = scenegen.make_scene(4, env_ids=ids, episode=s + 1)
+            o.load_scene(fresh, env_ids=ids)
+            o.set("min_margin", np.full((len(ids), 1), np.inf), ids)
+            b.reset(k2d.pack_scenes(caps, fresh), env_ids=ids)
+            n_reset += len(ids)
+    assert n_reset > steps
+    gs, os_ = b.state_dict(), o.state()
+    res = parity.compare(gs, os_, atol=1e-3, rtol=1e-3)
+    parity.assert_parity(res, "hetero with resets")
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+
+
+# ------------------------------------------------------------------------------------------ edge cases
+def _hand_scene_parity(sb, prm, steps, n_envs=1):
+    sc = sb.scene()
+    caps = sb.caps
+    act = np.zeros((steps, n_envs, caps[2] + caps[3]), dtype=np.float32)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b = parity.run_gpu(caps, prm, sc, act)
+    gs, os_ = b.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    return gs, os_
+
+
+def test_single_environment_and_empty_scene():
+    caps = scenegen.CAPS["S"]
+    sb = SceneBuilder(caps)                      # nothing active at all
+    gs, _ = _hand_scene_parity(sb, mkparams(), 3)
+    assert np.all(gs["pos"] == 0) and np.all(gs["pair_count"] == 0)
+    sb = SceneBuilder(caps)
+    sb.box(5.0, 0.1, (0, 0), static=True)
+    sb.box(0.3, 0.3, (0.2, 0.45), theta=0.3)
+    sb.circle(0.2, (-1.0, 0.35))
+    gs, os_ = _hand_scene_parity(sb, mkparams(n_substeps=2, n_iters=6), 50)
+    assert os_["pair_count"].sum() >= 2
+
+
+def test_pile_deeper_than_the_lds_pool():
+    """All 16 shapes of an L scene dumped onto one spot: far more active pairs than the per-environment
+    LDS pool holds, so the overflow path through the HBM record is exercised."""
+    caps = scenegen.CAPS["L"]
+    sb = SceneBuilder(caps, n_envs=3)
+    rng = np.random.default_rng(5)
+    for e in range(3):
+        sb.box(6.0, 0.1, (0, 0), static=True, e=e)
+        for k in range(11):
+            sb.box(0.3 + 0.02 * k, 0.25, (0.05 * k + 0.01 * e, 0.5 + 0.04 * k), theta=0.1 * k, friction=0.4, e=e)
+        for k in range(4):
+            sb.circle(0.3, (0.1 * k, 0.6 + 0.05 * k), e=e)
+    prm = mkparams(n_substeps=3, n_iters=10, alpha=0.5, beta=0.02)   # gentle corrections: the pile persists
+    sc = sb.scene()
+    act = np.zeros((6, 3, caps[2] + caps[3]), dtype=np.float32)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b = parity.run_gpu(caps, prm, sc, act)
+    gs, os_ = b.state_dict(), o.state()
+    assert (os_["pair_count"] > 0).sum(1).max() > 40
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+
+
+def test_triangles_circles_inside_polygons_and_static_joints():
+    caps = scenegen.CAPS["M"]
+    sb = SceneBuilder(caps)
+    f = sb.box(5.0, 0.1, (0, 0), static=True)
+    tri = np.array([[-0.4, -0.2], [0.4, -0.2], [0.0, 0.4]])
+    t = sb.polygon(tri, (0.0, 0.5), theta=2.0)
+    big = sb.box(0.6, 0.6, (2.0, 0.8))
+    c_in = sb.circle(0.1, (2.05, 0.85))              # centre inside the box
+    c2 = sb.circle(0.25, (0.1, 1.2))
+    sb.joint(f, t, (0.0, 0.5), motor_on=True, speed=2.0, power=0.5)   # hinge on a static shape
+    sb.joint(big, c2, (1.5, 1.0), fixed=True)
+    _hand_scene_parity(sb, mkparams(n_substeps=2, n_iters=8), 40)
+
+
+# ------------------------------------------------------------------------- full sizes, sampled outputs
+@pytest.mark.parametrize("cfg,steps,n_sample", [(0, 200, 64), (1, 256, 128), (2, 256, 192), (3, 128, 96),
+                                                (4, 256, 128)])
+def test_full_size_launch_sampled_against_oracle(cfg, steps, n_sample):
+    """The launch configuration the benchmark times (full environment count, all steps in one launch);
+    environments are independent, so the oracle recomputes a seeded sample of them one by one."""
+    import torch
+    import paper_2410_23208_amd as k2d
+    c = scenegen.CONFIGS[cfg]
+    n = c["n_envs"]
+    caps, prm, sc = scenegen.make_scene(cfg)
+    act = scenegen.make_actions(cfg, steps, n)
+    b = k2d.Batch(caps, n, prm)
+    b.reset(k2d.pack_scenes(caps, sc))
+    b.step(torch.from_numpy(act).cuda(), steps)
+    ids = np.sort(np.random.default_rng(cfg).choice(n, size=min(n, n_sample), replace=False))
+    ids[-1] = n - 1                                   # always include the last environment (ragged tail)
+    gs = k2d.unpack_state(caps, b.read_state()[torch.from_numpy(ids).cuda()].cpu().numpy())
+    o = parity.run_oracle(caps, prm, scenegen.select_envs(sc, ids), act[:, ids])
+    os_ = o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    # properties that hold at any size, over the whole batch
+    full = k2d.unpack_state(caps, b.read_state().cpu().numpy())
+    act_mask = np.repeat(full["active"] > 0, 2, axis=1)
+    assert np.isfinite(full["pos"][act_mask]).mean() > 0.999
+    static = np.repeat((sc["inv_mass"] == 0), 2, axis=1)
+    assert np.array_equal(full["pos"][static], np.asarray(sc["pos"]).reshape(n, -1)[static])
+
+
+def test_long_rollout_statistics():
+    """Beyond the element-wise horizon: distribution statistics of a 256-step rollout agree."""
+    b, o, caps = _both(2, 515, 256)
+    gs, os_ = b.state_dict(), o.state()
+    for stat in (np.nanmean, np.nanstd):
+        for k in ("vel", "omega"):
+            assert abs(stat(gs[k]) - stat(os_[k])) <= 1e-3 * (abs(stat(os_[k])) + 1.0)
+    hg = np.bincount((gs["pair_count"] > 0).sum(1).astype(int), minlength=40)
+    ho = np.bincount((os_["pair_count"] > 0).sum(1).astype(int), minlength=40)
+    assert np.abs(hg - ho).sum() <= 0.02 * len(gs["pos"])
+    assert not np.isnan(gs["pos"]).any()
