@@ -113,7 +113,10 @@ struct Cfg {
   static constexpr int X_WV = align_up(X_JOINED + N, 2);   // world vertices, float2 [4][P]
   static constexpr int X_WN = X_WV + 8 * P;                // outward unit edge normals, float2 [4][P]
   static constexpr int X_TABLE = X_WN + 8 * P;             // bytes [R][G]: pool index of pair (r, k)
-  static constexpr int X_POOL = X_TABLE + (R * G + 3) / 4;
+  static constexpr int X_SCHED = X_TABLE + (R * G + 3) / 4;    // bytes [R][G]: pool indices of each level
+  static constexpr int X_CNT = X_SCHED + (R * G + 3) / 4;      // words [R]: pairs in each level
+  static constexpr int X_BL = X_CNT + R;                       // bytes [N]: next free level of every shape
+  static constexpr int X_POOL = X_BL + (N + 3) / 4;
   static constexpr int LDS_WORDS = X_POOL + POOL * kRecW;
   // stride = odd multiple of G words: the same word of different environments falls into different banks
   static constexpr int LDS_STRIDE = align_up(LDS_WORDS - G, 2 * G) + G;
@@ -568,10 +571,12 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
     t_power = E[L.thr_power + k];
   }
   // pairs: lane k owns pair k of every round; eligibility is fixed for the launch
-  unsigned elig = 0u, prev_bits = 0u;
+  unsigned elig = 0u, prev_bits = 0u, pp_mask = 0u, pc_mask = 0u;
   for (int r = 0; r < R; ++r) {
     int a, b;
     if (S::sched_pair(r, k, a, b)) {
+      if (b < P) pp_mask |= 1u << r;
+      else if (a < P) pc_mask |= 1u << r;
       bool ok = (f2i(E[L.shape_flags + a]) & 1) && (f2i(E[L.shape_flags + b]) & 1) &&
                 !((f2i(E[K::X_JOINED + a]) >> b) & 1) && (E[L.inv_mass + a] + E[L.inv_mass + b]) > 0.f;
       if (ok) {
@@ -584,6 +589,9 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
     }
   }
   unsigned char* table = reinterpret_cast<unsigned char*>(E + K::X_TABLE);
+  unsigned char* sched = reinterpret_cast<unsigned char*>(E + K::X_SCHED);
+  unsigned char* blevel = reinterpret_cast<unsigned char*>(E + K::X_BL);
+  int* lcount = reinterpret_cast<int*>(E + K::X_CNT);
   float* pool = E + K::X_POOL;
   float* spill = Rg + K::G_SPILL;
   const float h = prm.h;
@@ -679,23 +687,35 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       }
 
       // ---- collision manifolds of all eligible pairs (A.3.1-A.3.4) and their substep constants ----
-      unsigned my_rounds = 0u, new_bits = 0u;
-      int pool_base = 0;
+      // First the cheap test for all of this lane's pairs: bounding circles apart (with margin) means no
+      // manifold point can have positive penetration.  Then the surviving pairs, one shape-type
+      // combination at a time, so that a wavefront runs one kind of manifold code per trip and makes
+      // only as many trips as its busiest lane has candidates.
+      unsigned cand = 0u;
+#pragma unroll
       for (int r = 0; r < R; ++r) {
-        Manifold m;
-        int a = 0, b = 0;
-        bool cand = (elig >> r) & 1u;
-        if (cand) {
+        if ((elig >> r) & 1u) {
+          int a, b;
           S::sched_pair(r, k, a, b);
-          // bounding circles apart (with margin): no manifold point can have positive penetration
           float dx = E[L.pos_x + b] - E[L.pos_x + a], dy = E[L.pos_y + b] - E[L.pos_y + a];
           float rr = (E[K::X_BRAD + a] + E[K::X_BRAD + b]) * 1.0001f + 1e-5f;
-          cand = dx * dx + dy * dy <= rr * rr;
+          if (dx * dx + dy * dy <= rr * rr) cand |= 1u << r;
         }
-        if (cand) {
-          if (b < P) {
+      }
+      unsigned my_rounds = 0u, new_bits = 0u;
+      int pool_base = 0;
+      for (int kind = 0; kind < 3; ++kind) {
+       unsigned todo = cand & (kind == 0 ? pp_mask : kind == 1 ? pc_mask : ~(pp_mask | pc_mask));
+       while (__any(todo != 0u)) {
+        Manifold m;
+        int a = 0, b = 0, r = 0;
+        if (todo != 0u) {
+          r = __ffs(todo) - 1;
+          todo &= todo - 1u;
+          S::sched_pair(r, k, a, b);
+          if (kind == 0) {
             S::manifold_pp(E, a, f2i(E[L.n_verts + a]), b, f2i(E[L.n_verts + b]), prm.tie_eps, m);
-          } else if (a < P) {
+          } else if (kind == 1) {
             S::manifold_pc(E, a, f2i(E[L.n_verts + a]), E[L.pos_x + b], E[L.pos_y + b], E[L.radius + (b - P)], m);
           } else {
             S::manifold_cc(E[L.pos_x + a], E[L.pos_y + a], E[L.radius + (a - P)], E[L.pos_x + b], E[L.pos_y + b],
@@ -755,16 +775,49 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           my_rounds |= 1u << r;
           new_bits |= ((unsigned)act0 | ((unsigned)act1 << 1)) << (2 * r);
         }
+       }
       }
       prev_bits = new_bits;
       unsigned env_rounds = my_rounds;
       for (int o = 1; o < G; o <<= 1) env_rounds |= __shfl_xor(env_rounds, o, G);
+      for (int i = k; i < N; i += G) blevel[i] = 0;
+      for (int i = k; i < R; i += G) lcount[i] = 0;
       __syncthreads();
+      // Dependency levels of the active pairs.  Walking the pairs in canonical order, a pair goes one
+      // level after the last earlier pair that shares a shape with it.  Pairs of one level touch
+      // disjoint shapes and pairs that share a shape keep their canonical order, so sweeping the levels
+      // in order, each level at once, gives the same bits as the sequential sweep -- in fewer trips than
+      // the rounds (a level never exceeds the pair's round).
+      for_each_round(env_rounds, my_rounds, [&](int r) {
+        int a, b;
+        S::sched_pair(r, k, a, b);
+        int lv = max((int)blevel[a], (int)blevel[b]);
+        blevel[a] = (unsigned char)(lv + 1);
+        blevel[b] = (unsigned char)(lv + 1);
+        int slot = atomicAdd(&lcount[lv], 1);
+        sched[lv * G + slot] = table[r * G + k];
+      });
+      unsigned long long level_cnt = 0ull;   // 4 bits per level: pairs in it
+      int n_clevels = 0;
+      for (int lv = 0; lv < R; ++lv) {
+        int c = lcount[lv];
+        level_cnt |= (unsigned long long)c << (4 * lv);
+        if (c > 0) n_clevels = lv + 1;
+      }
+      int wave_clevels = 0;
+      for (int lv = 1; lv <= R; ++lv)
+        if (__any(n_clevels >= lv)) wave_clevels = lv;
+      // every lane may now serve any pair: lane s of the group takes entry s of the level
+      auto for_each_level = [&](auto&& f) {
+        for (int lv = 0; lv < wave_clevels; ++lv) {
+          if (k < (int)((level_cnt >> (4 * lv)) & 15ull)) f((int)sched[lv * G + k]);
+          __syncthreads();
+        }
+      };
 
       // ---- warm starting (Alg. 1, A.7): collisions in canonical order, then joints ----
       if (prm.warm_start) {
-        for_each_round(env_rounds, my_rounds, [&](int r) {
-          int idx = table[r * G + k];
+        for_each_level([&](int idx) {
           PairRec rc;
           rec_load(idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW, rc);
           S::warm_pair(E, rc);
@@ -813,8 +866,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           }
           __syncthreads();
         }
-        for_each_round(env_rounds, my_rounds, [&](int r) {
-          int idx = table[r * G + k];
+        for_each_level([&](int idx) {
           float* rp = idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW;
           PairRec rc;
           rec_load(rp, rc);
@@ -840,8 +892,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       __syncthreads();
 
       // ---- positional corrections (A.3.7, A.4.1); the pair's accumulated impulses go to HBM ----
-      for_each_round(env_rounds, my_rounds, [&](int r) {
-        int idx = table[r * G + k];
+      for_each_level([&](int idx) {
         const float* rp = idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW;
         const float nx = rp[0], ny = rp[1], corr = rp[3];
         const int ab = f2i(rp[4]);
@@ -851,10 +902,19 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         E[L.pos_y + a] = E[L.pos_y + a] - (ima * corr) * ny;
         E[L.pos_x + b] = E[L.pos_x + b] + (imb * corr) * nx;
         E[L.pos_y + b] = E[L.pos_y + b] + (imb * corr) * ny;
-        if (env_ok)
-          *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(a, b)) =
-              make_float4(rp[13], rp[14], rp[23], rp[24]);
       });
+      // the owner of each active pair keeps its accumulated impulses in the HBM record for the next
+      // substep (only the owner ever reads or writes them there)
+      if (env_ok) {
+        for (unsigned rm = my_rounds; rm != 0u; rm &= rm - 1u) {
+          int r = __ffs(rm) - 1;
+          int idx = table[r * G + k];
+          const float* rp = idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW;
+          const int ab = f2i(rp[4]);
+          *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(ab & 0xff, (ab >> 8) & 0xff)) =
+              make_float4(rp[13], rp[14], rp[23], rp[24]);
+        }
+      }
       for (int lv = 0; lv < wave_levels; ++lv) {
         if (k < J && j_live && j_level == lv) {
           float ca = E[K::X_COS + ja], sa = E[K::X_SIN + ja], cb = E[K::X_COS + jb], sb = E[K::X_SIN + jb];
