@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=2, help="workload 0..4 (default 2 = L, 8192 envs x 256 steps)")
     ap.add_argument("--cpu-envs", type=int, default=2048, help="environments of the CPU-oracle sample")
+    ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain 256 MiB device copy, so "
+                    "that a counter run has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg (flop model then uses "
                     "a 256-environment oracle run only for the contact statistics)")
     args = ap.parse_args()
@@ -77,6 +79,12 @@ def main():
         if ev:
             ev[1].record()
 
+    if args.calibrate_copy:
+        src = torch.empty(64 << 20, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         one_pass()
     torch.cuda.synchronize()
