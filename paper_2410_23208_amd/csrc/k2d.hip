@@ -113,8 +113,10 @@ struct Cfg {
   static constexpr int X_WV = align_up(X_JOINED + N, 2);   // world vertices, float2 [4][P]
   static constexpr int X_WN = X_WV + 8 * P;                // outward unit edge normals, float2 [4][P]
   static constexpr int X_TABLE = X_WN + 8 * P;             // bytes [R][G]: pool index of pair (r, k)
-  static constexpr int X_SCHED = X_TABLE + (R * G + 3) / 4;    // bytes [R][G]: pool indices of each level
-  static constexpr int X_CNT = X_SCHED + (R * G + 3) / 4;      // words [R]: pairs in each level
+  static constexpr int X_SCHED = X_TABLE + (R * G + 3) / 4;    // bytes [R*G]: pool indices, level after level
+  static constexpr int X_LVL = X_SCHED + (R * G + 3) / 4;      // bytes [R][G]: level of pair (r, k)
+  static constexpr int X_SLOT = X_LVL + (R * G + 3) / 4;       // bytes [R][G]: its place inside the level
+  static constexpr int X_CNT = X_SLOT + (R * G + 3) / 4;       // words [R]: pairs in each level
   static constexpr int X_BL = X_CNT + R;                       // bytes [N]: next free level of every shape
   static constexpr int X_POOL = X_BL + (N + 3) / 4;
   static constexpr int LDS_WORDS = X_POOL + POOL * kRecW;
@@ -377,7 +379,7 @@ struct Step {
 
   // One visit of an active pair in a solver sweep: per point, normal impulse then friction impulse,
   // accumulated and clamped (A.3.5, A.3.6, A.7).  Velocities are read from and written to LDS.
-  static __device__ __forceinline__ void solve_pair(float* E, PairRec& rc) {
+  static __device__ __forceinline__ void solve_pair(float* E, PairRec& rc, unsigned fixed) {
     const int a = rc.ab & 0xff, b = (rc.ab >> 8) & 0xff;
     float vax = E[L.vel_x + a], vay = E[L.vel_y + a], wa = E[L.omega + a];
     float vbx = E[L.vel_x + b], vby = E[L.vel_y + b], wb = E[L.omega + b];
@@ -413,12 +415,12 @@ struct Step {
         wb = wb + iib * (rc.rbx[k] * (-fy) - rc.rby[k] * (-fx));
       }
     }
-    E[L.vel_x + a] = vax; E[L.vel_y + a] = vay; E[L.omega + a] = wa;
-    E[L.vel_x + b] = vbx; E[L.vel_y + b] = vby; E[L.omega + b] = wb;
+    if (!((fixed >> a) & 1u)) { E[L.vel_x + a] = vax; E[L.vel_y + a] = vay; E[L.omega + a] = wa; }
+    if (!((fixed >> b) & 1u)) { E[L.vel_x + b] = vbx; E[L.vel_y + b] = vby; E[L.omega + b] = wb; }
   }
 
   // Warm starting of one pair (A.7): re-apply the kept accumulated impulses.
-  static __device__ __forceinline__ void warm_pair(float* E, const PairRec& rc) {
+  static __device__ __forceinline__ void warm_pair(float* E, const PairRec& rc, unsigned fixed) {
     const int a = rc.ab & 0xff, b = (rc.ab >> 8) & 0xff;
     float vax = E[L.vel_x + a], vay = E[L.vel_y + a], wa = E[L.omega + a];
     float vbx = E[L.vel_x + b], vby = E[L.vel_y + b], wb = E[L.omega + b];
@@ -436,8 +438,8 @@ struct Step {
         wb = wb + iib * (rc.rbx[k] * (-jy) - rc.rby[k] * (-jx));
       }
     }
-    E[L.vel_x + a] = vax; E[L.vel_y + a] = vay; E[L.omega + a] = wa;
-    E[L.vel_x + b] = vbx; E[L.vel_y + b] = vby; E[L.omega + b] = wb;
+    if (!((fixed >> a) & 1u)) { E[L.vel_x + a] = vax; E[L.vel_y + a] = vay; E[L.omega + a] = wa; }
+    if (!((fixed >> b) & 1u)) { E[L.vel_x + b] = vbx; E[L.vel_y + b] = vby; E[L.omega + b] = wb; }
   }
 };
 
@@ -534,8 +536,16 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
     E[L.joint_flags + k] = i2f((fl & 7) | (j_live ? 8 : 0));
   }
   __syncthreads();
+  // Shapes that no impulse can move (no inverse mass, no inverse inertia; inactive ones too).  An
+  // impulse leaves their velocity and position exactly as they are, so constraints that share only
+  // such a shape do not depend on each other, and nothing is ever written back for them.
+  unsigned static_mask = 0u;
+  for (int i = 0; i < N; ++i)
+    if (!(f2i(E[L.shape_flags + i]) & 1) || (E[L.inv_mass + i] == 0.f && E[L.inv_inertia + i] == 0.f))
+      static_mask |= 1u << i;
+  const bool ja_fix = (static_mask >> ja) & 1u, jb_fix = (static_mask >> jb) & 1u;
   // dependency levels of the joints: a joint runs one level after the last earlier joint that shares a
-  // shape with it, so joints sharing a shape keep their index order and the others run side by side
+  // movable shape with it, so joints sharing a shape keep their index order, the others run side by side
   int j_level = 0, n_levels = 0;
   {
     unsigned long long last = 0ull;   // 4 bits per shape: next free level
@@ -543,12 +553,13 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       int fl = f2i(E[L.joint_flags + q]);
       if (fl & 8) {
         int a = f2i(E[L.joint_a + q]), b = f2i(E[L.joint_b + q]);
-        int la = (int)((last >> (4 * a)) & 15ull), lb = (int)((last >> (4 * b)) & 15ull);
+        const bool da = !((static_mask >> a) & 1u), db = !((static_mask >> b) & 1u);
+        int la = da ? (int)((last >> (4 * a)) & 15ull) : 0, lb = db ? (int)((last >> (4 * b)) & 15ull) : 0;
         int lv = max(la, lb);
         if (q == k) j_level = lv;
         n_levels = max(n_levels, lv + 1);
-        last &= ~((15ull << (4 * a)) | (15ull << (4 * b)));
-        last |= ((unsigned long long)(lv + 1) << (4 * a)) | ((unsigned long long)(lv + 1) << (4 * b));
+        if (da) last = (last & ~(15ull << (4 * a))) | ((unsigned long long)(lv + 1) << (4 * a));
+        if (db) last = (last & ~(15ull << (4 * b))) | ((unsigned long long)(lv + 1) << (4 * b));
       }
     }
   }
@@ -591,6 +602,8 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
   unsigned char* table = reinterpret_cast<unsigned char*>(E + K::X_TABLE);
   unsigned char* sched = reinterpret_cast<unsigned char*>(E + K::X_SCHED);
   unsigned char* blevel = reinterpret_cast<unsigned char*>(E + K::X_BL);
+  unsigned char* lvl_of = reinterpret_cast<unsigned char*>(E + K::X_LVL);
+  unsigned char* slot_of = reinterpret_cast<unsigned char*>(E + K::X_SLOT);
   int* lcount = reinterpret_cast<int*>(E + K::X_CNT);
   float* pool = E + K::X_POOL;
   float* spill = Rg + K::G_SPILL;
@@ -671,8 +684,8 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       __syncthreads();
       for (int lv = 0; lv < wave_levels; ++lv) {
         if (k < J && j_live && j_level == lv && motor != 0.f) {
-          E[L.omega + ja] = E[L.omega + ja] - j_iia * motor;
-          E[L.omega + jb] = E[L.omega + jb] + j_iib * motor;
+          if (!ja_fix) E[L.omega + ja] = E[L.omega + ja] - j_iia * motor;
+          if (!jb_fix) E[L.omega + jb] = E[L.omega + jb] + j_iib * motor;
         }
         __syncthreads();
       }
@@ -784,34 +797,51 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       for (int i = k; i < R; i += G) lcount[i] = 0;
       __syncthreads();
       // Dependency levels of the active pairs.  Walking the pairs in canonical order, a pair goes one
-      // level after the last earlier pair that shares a shape with it.  Pairs of one level touch
-      // disjoint shapes and pairs that share a shape keep their canonical order, so sweeping the levels
-      // in order, each level at once, gives the same bits as the sequential sweep -- in fewer trips than
-      // the rounds (a level never exceeds the pair's round).
+      // level after the last earlier pair that shares a movable shape with it.  Pairs of one level touch
+      // disjoint movable shapes and pairs that share one keep their canonical order, so sweeping the
+      // levels in order, each level at once, gives the same bits as the sequential sweep -- in far fewer
+      // trips (everything resting on the static floor is one level; a level never exceeds the round).
       for_each_round(env_rounds, my_rounds, [&](int r) {
         int a, b;
         S::sched_pair(r, k, a, b);
-        int lv = max((int)blevel[a], (int)blevel[b]);
-        blevel[a] = (unsigned char)(lv + 1);
-        blevel[b] = (unsigned char)(lv + 1);
-        int slot = atomicAdd(&lcount[lv], 1);
-        sched[lv * G + slot] = table[r * G + k];
+        const bool da = !((static_mask >> a) & 1u), db = !((static_mask >> b) & 1u);
+        int lv = max(da ? (int)blevel[a] : 0, db ? (int)blevel[b] : 0);
+        if (da) blevel[a] = (unsigned char)(lv + 1);
+        if (db) blevel[b] = (unsigned char)(lv + 1);
+        lvl_of[r * G + k] = (unsigned char)lv;
+        slot_of[r * G + k] = (unsigned char)atomicAdd(&lcount[lv], 1);
       });
-      unsigned long long level_cnt = 0ull;   // 4 bits per level: pairs in it
+      // sizes and start offsets of the levels, 8 bits each
+      unsigned long long cnt_lo = 0ull, cnt_hi = 0ull, off_lo = 0ull, off_hi = 0ull;
       int n_clevels = 0;
-      for (int lv = 0; lv < R; ++lv) {
-        int c = lcount[lv];
-        level_cnt |= (unsigned long long)c << (4 * lv);
-        if (c > 0) n_clevels = lv + 1;
+      {
+        int run = 0;
+        for (int lv = 0; lv < R; ++lv) {
+          int c = lcount[lv];
+          if (lv < 8) { cnt_lo |= (unsigned long long)c << (8 * lv); off_lo |= (unsigned long long)run << (8 * lv); }
+          else { cnt_hi |= (unsigned long long)c << (8 * (lv - 8)); off_hi |= (unsigned long long)run << (8 * (lv - 8)); }
+          run += c;
+          if (c > 0) n_clevels = lv + 1;
+        }
+      }
+      auto cnt_of = [&](int lv) { return (int)(((lv < 8) ? (cnt_lo >> (8 * lv)) : (cnt_hi >> (8 * (lv - 8)))) & 255ull); };
+      auto off_of = [&](int lv) { return (int)(((lv < 8) ? (off_lo >> (8 * lv)) : (off_hi >> (8 * (lv - 8)))) & 255ull); };
+      for (unsigned rm = my_rounds; rm != 0u; rm &= rm - 1u) {
+        int r = __ffs(rm) - 1;
+        sched[off_of(lvl_of[r * G + k]) + slot_of[r * G + k]] = table[r * G + k];
       }
       int wave_clevels = 0;
       for (int lv = 1; lv <= R; ++lv)
         if (__any(n_clevels >= lv)) wave_clevels = lv;
-      // every lane may now serve any pair: lane s of the group takes entry s of the level
+      __syncthreads();
+      // every lane may now serve any pair: the lanes of the group take the entries of a level G at a time
       auto for_each_level = [&](auto&& f) {
         for (int lv = 0; lv < wave_clevels; ++lv) {
-          if (k < (int)((level_cnt >> (4 * lv)) & 15ull)) f((int)sched[lv * G + k]);
-          __syncthreads();
+          const int c = cnt_of(lv), o = off_of(lv);
+          for (int base = 0; __any(base < c); base += G) {
+            if (base + k < c) f((int)sched[o + base + k]);
+            __syncthreads();
+          }
         }
       };
 
@@ -820,7 +850,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         for_each_level([&](int idx) {
           PairRec rc;
           rec_load(idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW, rc);
-          S::warm_pair(E, rc);
+          S::warm_pair(E, rc, static_mask);
         });
         for (int lv = 0; lv < wave_levels; ++lv) {
           if (k < J && j_live && j_level == lv) {
@@ -829,12 +859,16 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
               wa = wa + j_iia * j_acca;
               wb = wb - j_iib * j_acca;
             }
-            E[L.vel_x + ja] = E[L.vel_x + ja] + j_ima * j_accx;
-            E[L.vel_y + ja] = E[L.vel_y + ja] + j_ima * j_accy;
-            E[L.omega + ja] = wa + j_iia * (j_rax * j_accy - j_ray * j_accx);
-            E[L.vel_x + jb] = E[L.vel_x + jb] + j_imb * (-j_accx);
-            E[L.vel_y + jb] = E[L.vel_y + jb] + j_imb * (-j_accy);
-            E[L.omega + jb] = wb + j_iib * (j_rbx * (-j_accy) - j_rby * (-j_accx));
+            if (!ja_fix) {
+              E[L.vel_x + ja] = E[L.vel_x + ja] + j_ima * j_accx;
+              E[L.vel_y + ja] = E[L.vel_y + ja] + j_ima * j_accy;
+              E[L.omega + ja] = wa + j_iia * (j_rax * j_accy - j_ray * j_accx);
+            }
+            if (!jb_fix) {
+              E[L.vel_x + jb] = E[L.vel_x + jb] + j_imb * (-j_accx);
+              E[L.vel_y + jb] = E[L.vel_y + jb] + j_imb * (-j_accy);
+              E[L.omega + jb] = wb + j_iib * (j_rbx * (-j_accy) - j_rby * (-j_accx));
+            }
           }
           __syncthreads();
         }
@@ -861,8 +895,8 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
             vbx = vbx + j_imb * (-jx); vby = vby + j_imb * (-jy);
             wb = wb + j_iib * (j_rbx * (-jy) - j_rby * (-jx));
             j_accx = j_accx + jx; j_accy = j_accy + jy;
-            E[L.vel_x + ja] = vax; E[L.vel_y + ja] = vay; E[L.omega + ja] = wa;
-            E[L.vel_x + jb] = vbx; E[L.vel_y + jb] = vby; E[L.omega + jb] = wb;
+            if (!ja_fix) { E[L.vel_x + ja] = vax; E[L.vel_y + ja] = vay; E[L.omega + ja] = wa; }
+            if (!jb_fix) { E[L.vel_x + jb] = vbx; E[L.vel_y + jb] = vby; E[L.omega + jb] = wb; }
           }
           __syncthreads();
         }
@@ -870,7 +904,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           float* rp = idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW;
           PairRec rc;
           rec_load(rp, rc);
-          S::solve_pair(E, rc);
+          S::solve_pair(E, rc, static_mask);
 #pragma unroll
           for (int q = 0; q < 2; ++q) { rp[5 + 10 * q + 8] = rc.lam_n[q]; rp[5 + 10 * q + 9] = rc.lam_t[q]; }
         });
@@ -898,10 +932,14 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         const int ab = f2i(rp[4]);
         const int a = ab & 0xff, b = (ab >> 8) & 0xff;
         const float ima = E[L.inv_mass + a], imb = E[L.inv_mass + b];
-        E[L.pos_x + a] = E[L.pos_x + a] - (ima * corr) * nx;
-        E[L.pos_y + a] = E[L.pos_y + a] - (ima * corr) * ny;
-        E[L.pos_x + b] = E[L.pos_x + b] + (imb * corr) * nx;
-        E[L.pos_y + b] = E[L.pos_y + b] + (imb * corr) * ny;
+        if (!((static_mask >> a) & 1u)) {
+          E[L.pos_x + a] = E[L.pos_x + a] - (ima * corr) * nx;
+          E[L.pos_y + a] = E[L.pos_y + a] - (ima * corr) * ny;
+        }
+        if (!((static_mask >> b) & 1u)) {
+          E[L.pos_x + b] = E[L.pos_x + b] + (imb * corr) * nx;
+          E[L.pos_y + b] = E[L.pos_y + b] + (imb * corr) * ny;
+        }
       });
       // the owner of each active pair keeps its accumulated impulses in the HBM record for the next
       // substep (only the owner ever reads or writes them there)
@@ -922,10 +960,14 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           float xbx = E[L.pos_x + jb] + (cb * j_abx - sb * j_aby), xby = E[L.pos_y + jb] + (sb * j_abx + cb * j_aby);
           float cf = prm.joint_beta / (j_ima + j_imb);
           float cx = cf * (xax - xbx), cy = cf * (xay - xby);
-          E[L.pos_x + ja] = E[L.pos_x + ja] - j_ima * cx;
-          E[L.pos_y + ja] = E[L.pos_y + ja] - j_ima * cy;
-          E[L.pos_x + jb] = E[L.pos_x + jb] + j_imb * cx;
-          E[L.pos_y + jb] = E[L.pos_y + jb] + j_imb * cy;
+          if (!ja_fix) {
+            E[L.pos_x + ja] = E[L.pos_x + ja] - j_ima * cx;
+            E[L.pos_y + ja] = E[L.pos_y + ja] - j_ima * cy;
+          }
+          if (!jb_fix) {
+            E[L.pos_x + jb] = E[L.pos_x + jb] + j_imb * cx;
+            E[L.pos_y + jb] = E[L.pos_y + jb] + j_imb * cy;
+          }
         }
         __syncthreads();
       }
@@ -1080,7 +1122,9 @@ __global__ void k2d_contacts_kernel(const float* state, uint8_t* pair_count, uin
 // ---------------------------------------------------------------------------------------------------
 using CfgS = Cfg<5, 2, 1, 1, 21>;
 using CfgM = Cfg<6, 3, 2, 2, 36>;
-using CfgL = Cfg<12, 4, 6, 2, 20>;
+using CfgL = Cfg<12, 4, 6, 2, 18>;
+// four L wavefronts must share one CU's 160 KiB of LDS: with 8192 environments every SIMD then holds one
+static_assert(CfgL::LDS_BYTES <= 40960, "L image too large for four wavefronts per CU");
 
 int caps_class(const k2d_caps* c) {
   if (!c) return -1;
