@@ -184,20 +184,28 @@ struct PairRec {
   float rax[2], ray[2], rbx[2], rby[2], mass_n[2], mass_t[2], bias[2], rest[2], lam_n[2], lam_t[2];
 };
 
-__device__ __forceinline__ void rec_store(float* p, const PairRec& r) {
+// LDS pointers are passed with their address space spelled out, so that a record access can never
+// degrade into a flat access when the LDS and the HBM (spill) variants of a code path are merged.
+using LdsF = __attribute__((address_space(3))) float*;
+using LdsCF = const __attribute__((address_space(3))) float*;
+__device__ __forceinline__ LdsF to_lds(float* p) { return (LdsF)p; }
+
+template <class Ptr>
+__device__ __forceinline__ void rec_store(Ptr p, const PairRec& r) {
   p[0] = r.nx; p[1] = r.ny; p[2] = r.mu; p[3] = r.corr; p[4] = i2f(r.ab);
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
-    float* q = p + 5 + 10 * k;
+    auto q = p + 5 + 10 * k;
     q[0] = r.rax[k]; q[1] = r.ray[k]; q[2] = r.rbx[k]; q[3] = r.rby[k]; q[4] = r.mass_n[k];
     q[5] = r.mass_t[k]; q[6] = r.bias[k]; q[7] = r.rest[k]; q[8] = r.lam_n[k]; q[9] = r.lam_t[k];
   }
 }
-__device__ __forceinline__ void rec_load(const float* p, PairRec& r) {
+template <class Ptr>
+__device__ __forceinline__ void rec_load(Ptr p, PairRec& r) {
   r.nx = p[0]; r.ny = p[1]; r.mu = p[2]; r.corr = p[3]; r.ab = f2i(p[4]);
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
-    const float* q = p + 5 + 10 * k;
+    auto q = p + 5 + 10 * k;
     r.rax[k] = q[0]; r.ray[k] = q[1]; r.rbx[k] = q[2]; r.rby[k] = q[3]; r.mass_n[k] = q[4];
     r.mass_t[k] = q[5]; r.bias[k] = q[6]; r.rest[k] = q[7]; r.lam_n[k] = q[8]; r.lam_t[k] = q[9];
   }
@@ -783,7 +791,8 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
             if (on) pen = fmaxf(pen, m.pen[q]);
           }
           rc.corr = prm.beta * fmaxf(pen - prm.slop, 0.f) / (ima + imb);          // A.3.7
-          rec_store(idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW, rc);
+          if (idx < K::POOL) rec_store(to_lds(pool + idx * kRecW), rc);
+          else rec_store(spill + (idx - K::POOL) * kRecW, rc);
           table[r * G + k] = (unsigned char)idx;
           my_rounds |= 1u << r;
           new_bits |= ((unsigned)act0 | ((unsigned)act1 << 1)) << (2 * r);
@@ -849,7 +858,8 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       if (prm.warm_start) {
         for_each_level([&](int idx) {
           PairRec rc;
-          rec_load(idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW, rc);
+          if (idx < K::POOL) rec_load(to_lds(pool + idx * kRecW), rc);
+          else rec_load(spill + (idx - K::POOL) * kRecW, rc);
           S::warm_pair(E, rc, static_mask);
         });
         for (int lv = 0; lv < wave_levels; ++lv) {
@@ -901,12 +911,22 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           __syncthreads();
         }
         for_each_level([&](int idx) {
-          float* rp = idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW;
+          // (the two branches keep LDS and HBM accesses apart: a merged pointer would turn every access
+          // into a slow flat one)
           PairRec rc;
-          rec_load(rp, rc);
-          S::solve_pair(E, rc, static_mask);
+          if (idx < K::POOL) {
+            LdsF rp = to_lds(pool + idx * kRecW);
+            rec_load(rp, rc);
+            S::solve_pair(E, rc, static_mask);
 #pragma unroll
-          for (int q = 0; q < 2; ++q) { rp[5 + 10 * q + 8] = rc.lam_n[q]; rp[5 + 10 * q + 9] = rc.lam_t[q]; }
+            for (int q = 0; q < 2; ++q) { rp[5 + 10 * q + 8] = rc.lam_n[q]; rp[5 + 10 * q + 9] = rc.lam_t[q]; }
+          } else {
+            float* rp = spill + (idx - K::POOL) * kRecW;
+            rec_load(rp, rc);
+            S::solve_pair(E, rc, static_mask);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) { rp[5 + 10 * q + 8] = rc.lam_n[q]; rp[5 + 10 * q + 9] = rc.lam_t[q]; }
+          }
         });
       }
 
@@ -927,9 +947,10 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
 
       // ---- positional corrections (A.3.7, A.4.1); the pair's accumulated impulses go to HBM ----
       for_each_level([&](int idx) {
-        const float* rp = idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW;
-        const float nx = rp[0], ny = rp[1], corr = rp[3];
-        const int ab = f2i(rp[4]);
+        float nx, ny, corr;
+        int ab;
+        if (idx < K::POOL) { LdsF rp = to_lds(pool + idx * kRecW); nx = rp[0]; ny = rp[1]; corr = rp[3]; ab = f2i(rp[4]); }
+        else { const float* rp = spill + (idx - K::POOL) * kRecW; nx = rp[0]; ny = rp[1]; corr = rp[3]; ab = f2i(rp[4]); }
         const int a = ab & 0xff, b = (ab >> 8) & 0xff;
         const float ima = E[L.inv_mass + a], imb = E[L.inv_mass + b];
         if (!((static_mask >> a) & 1u)) {
@@ -947,10 +968,11 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         for (unsigned rm = my_rounds; rm != 0u; rm &= rm - 1u) {
           int r = __ffs(rm) - 1;
           int idx = table[r * G + k];
-          const float* rp = idx < K::POOL ? pool + idx * kRecW : spill + (idx - K::POOL) * kRecW;
-          const int ab = f2i(rp[4]);
-          *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(ab & 0xff, (ab >> 8) & 0xff)) =
-              make_float4(rp[13], rp[14], rp[23], rp[24]);
+          int ab;
+          float4 lam;
+          if (idx < K::POOL) { LdsF rp = to_lds(pool + idx * kRecW); ab = f2i(rp[4]); lam = make_float4(rp[13], rp[14], rp[23], rp[24]); }
+          else { const float* rp = spill + (idx - K::POOL) * kRecW; ab = f2i(rp[4]); lam = make_float4(rp[13], rp[14], rp[23], rp[24]); }
+          *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(ab & 0xff, (ab >> 8) & 0xff)) = lam;
         }
       }
       for (int lv = 0; lv < wave_levels; ++lv) {
