@@ -109,16 +109,18 @@ struct Cfg {
   static constexpr int X_COS = align_up(L.scene_words, 2);
   static constexpr int X_SIN = X_COS + N;
   static constexpr int X_BRAD = X_SIN + N;       // bounding radius of every shape
-  static constexpr int X_JOINED = X_BRAD + N;    // bit j of word i: shapes i, j joined by a live joint
-  static constexpr int X_WV = align_up(X_JOINED + N, 2);   // world vertices, float2 [4][P]
+  static constexpr int X_WV = align_up(X_BRAD + N, 2);     // world vertices, float2 [4][P]
   static constexpr int X_WN = X_WV + 8 * P;                // outward unit edge normals, float2 [4][P]
-  static constexpr int X_TABLE = X_WN + 8 * P;             // bytes [R][G]: pool index of pair (r, k)
-  static constexpr int X_SCHED = X_TABLE + (R * G + 3) / 4;    // bytes [R*G]: pool indices, level after level
-  static constexpr int X_LVL = X_SCHED + (R * G + 3) / 4;      // bytes [R][G]: level of pair (r, k)
-  static constexpr int X_SLOT = X_LVL + (R * G + 3) / 4;       // bytes [R][G]: its place inside the level
-  static constexpr int X_CNT = X_SLOT + (R * G + 3) / 4;       // words [R]: pairs in each level
-  static constexpr int X_BL = X_CNT + R;                       // bytes [N]: next free level of every shape
-  static constexpr int X_POOL = X_BL + (N + 3) / 4;
+  static constexpr int NID = R * G;                        // pair ids: id = r * G + k (canonical order)
+  static constexpr int X_TABLE = align_up(X_WN + 8 * P, 4);        // bytes [NID]: pool index of pair id, 0xFF = none
+  static constexpr int TABLE_W = align_up((NID + 3) / 4, 4);       // read back four words at a time
+  static constexpr int X_LIST = X_TABLE + TABLE_W;         // bytes [NID]: candidate ids, one shape-type mix after the other
+  static constexpr int X_JOINED = X_LIST;                  // (launch set-up only) bit j of word i: shapes i, j joined
+  static constexpr int LIST_W = (NID + 3) / 4 > N ? (NID + 3) / 4 : N;
+  static constexpr int LCAP = 16;                          // a level holds at most one pair per movable shape
+  static constexpr int X_SCHED = X_LIST + LIST_W;          // bytes [R][LCAP]: pool indices, level by level
+  static constexpr int X_PSTATE = align_up(X_SCHED + R * LCAP / 4, 4);   // bytes [G][16]: active-point bits of pair (r, k) at [k][r]
+  static constexpr int X_POOL = X_PSTATE + G * 4;
   static constexpr int LDS_WORDS = X_POOL + POOL * kRecW;
   // stride = odd multiple of G words: the same word of different environments falls into different banks
   static constexpr int LDS_STRIDE = align_up(LDS_WORDS - G, 2 * G) + G;
@@ -451,22 +453,6 @@ struct Step {
   }
 };
 
-// Walks, for every environment of the wavefront, the rounds in which that environment has an active
-// pair, in round order; lane k of the group runs `f(r)` if its own pair of round r is active.  A fence
-// follows every round, so the next round sees this round's LDS writes.
-template <class F>
-__device__ __forceinline__ void for_each_round(unsigned env_rounds, unsigned my_rounds, F&& f) {
-  unsigned rm = env_rounds;
-  while (__any(rm != 0u)) {
-    if (rm != 0u) {
-      int r = __ffs(rm) - 1;
-      rm &= rm - 1u;
-      if ((my_rounds >> r) & 1u) f(r);
-    }
-    __syncthreads();
-  }
-}
-
 template <class K>
 __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state, const float* __restrict__ actions,
                                                       int n_envs, int n_steps, Params prm) {
@@ -589,8 +575,13 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
     k2d_sincos(E[L.thr_angle + k], t_dy, t_dx);
     t_power = E[L.thr_power + k];
   }
-  // pairs: lane k owns pair k of every round; eligibility is fixed for the launch
-  unsigned elig = 0u, prev_bits = 0u, pp_mask = 0u, pc_mask = 0u;
+  // pairs: lane k tests pair k of every round; eligibility is fixed for the launch
+  unsigned char* table = reinterpret_cast<unsigned char*>(E + K::X_TABLE);
+  unsigned char* cand_list = reinterpret_cast<unsigned char*>(E + K::X_LIST);
+  unsigned char* sched = reinterpret_cast<unsigned char*>(E + K::X_SCHED);
+  unsigned char* pstate = reinterpret_cast<unsigned char*>(E + K::X_PSTATE);
+  unsigned elig = 0u, pp_mask = 0u, pc_mask = 0u;
+  for (int r = 0; r < 16; ++r) pstate[k * 16 + r] = 0;
   for (int r = 0; r < R; ++r) {
     int a, b;
     if (S::sched_pair(r, k, a, b)) {
@@ -602,17 +593,12 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         elig |= 1u << r;
         if (env_ok) {
           const unsigned char* ps = reinterpret_cast<const unsigned char*>(Rg + L.pair_state);
-          prev_bits |= (unsigned)(ps[S::pair_index(a, b)] & 3) << (2 * r);
+          pstate[k * 16 + r] = ps[S::pair_index(a, b)] & 3;
         }
       }
     }
   }
-  unsigned char* table = reinterpret_cast<unsigned char*>(E + K::X_TABLE);
-  unsigned char* sched = reinterpret_cast<unsigned char*>(E + K::X_SCHED);
-  unsigned char* blevel = reinterpret_cast<unsigned char*>(E + K::X_BL);
-  unsigned char* lvl_of = reinterpret_cast<unsigned char*>(E + K::X_LVL);
-  unsigned char* slot_of = reinterpret_cast<unsigned char*>(E + K::X_SLOT);
-  int* lcount = reinterpret_cast<int*>(E + K::X_CNT);
+  __syncthreads();   // the joined-shape words share their LDS with the candidate list
   float* pool = E + K::X_POOL;
   float* spill = Rg + K::G_SPILL;
   const float h = prm.h;
@@ -708,10 +694,12 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       }
 
       // ---- collision manifolds of all eligible pairs (A.3.1-A.3.4) and their substep constants ----
-      // First the cheap test for all of this lane's pairs: bounding circles apart (with margin) means no
-      // manifold point can have positive penetration.  Then the surviving pairs, one shape-type
-      // combination at a time, so that a wavefront runs one kind of manifold code per trip and makes
-      // only as many trips as its busiest lane has candidates.
+      // 1. the cheap test for all of this lane's pairs: bounding circles apart (with margin) means no
+      //    manifold point can have positive penetration;
+      // 2. the surviving pair ids of the environment are gathered into one list, one shape-type mix
+      //    after the other, so that the group's lanes share them evenly and a wavefront runs one kind
+      //    of manifold code per trip;
+      // 3. every active pair becomes a record in the pool.
       unsigned cand = 0u;
 #pragma unroll
       for (int r = 0; r < R; ++r) {
@@ -723,17 +711,48 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           if (dx * dx + dy * dy <= rr * rr) cand |= 1u << r;
         }
       }
-      unsigned my_rounds = 0u, new_bits = 0u;
+      {   // pairs that were colliding and are not even candidates now: their points are no longer active
+        uint4 ps = *reinterpret_cast<const uint4*>(pstate + k * 16);
+        unsigned nz = 0u;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          unsigned w = r < 4 ? ps.x : r < 8 ? ps.y : r < 12 ? ps.z : ps.w;
+          if ((w >> (8 * (r & 3))) & 0xffu) nz |= 1u << r;
+        }
+        for (unsigned st = nz & ~cand; st != 0u; st &= st - 1u) pstate[k * 16 + (__ffs(st) - 1)] = 0;
+      }
+      for (int i = k; i < K::TABLE_W; i += G) reinterpret_cast<unsigned*>(table)[i] = 0xffffffffu;
+      int kind_n[3], kind_off[3];
+      {
+        const unsigned m0 = cand & pp_mask, m1 = cand & pc_mask, m2 = cand & ~(pp_mask | pc_mask);
+        const unsigned mine = (unsigned)__popc(m0) | ((unsigned)__popc(m1) << 8) | ((unsigned)__popc(m2) << 16);
+        unsigned incl = mine;
+        for (int d = 1; d < G; d <<= 1) {
+          unsigned up = __shfl_up(incl, d, G);
+          if (k >= d) incl += up;
+        }
+        const unsigned tot = __shfl(incl, G - 1, G), excl = incl - mine;
+        kind_n[0] = tot & 255; kind_n[1] = (tot >> 8) & 255; kind_n[2] = (tot >> 16) & 255;
+        kind_off[0] = 0; kind_off[1] = kind_n[0]; kind_off[2] = kind_n[0] + kind_n[1];
+        int w0 = kind_off[0] + (int)(excl & 255), w1 = kind_off[1] + (int)((excl >> 8) & 255);
+        int w2 = kind_off[2] + (int)((excl >> 16) & 255);
+        for (unsigned mm = m0; mm != 0u; mm &= mm - 1u) cand_list[w0++] = (unsigned char)((__ffs(mm) - 1) * G + k);
+        for (unsigned mm = m1; mm != 0u; mm &= mm - 1u) cand_list[w1++] = (unsigned char)((__ffs(mm) - 1) * G + k);
+        for (unsigned mm = m2; mm != 0u; mm &= mm - 1u) cand_list[w2++] = (unsigned char)((__ffs(mm) - 1) * G + k);
+      }
+      __syncthreads();
       int pool_base = 0;
       for (int kind = 0; kind < 3; ++kind) {
-       unsigned todo = cand & (kind == 0 ? pp_mask : kind == 1 ? pc_mask : ~(pp_mask | pc_mask));
-       while (__any(todo != 0u)) {
+       const int n_kind = kind_n[kind], off_kind = kind_off[kind];
+       for (int base = 0; __any(base < n_kind); base += G) {
         Manifold m;
-        int a = 0, b = 0, r = 0;
-        if (todo != 0u) {
-          r = __ffs(todo) - 1;
-          todo &= todo - 1u;
-          S::sched_pair(r, k, a, b);
+        int a = 0, b = 0, r = 0, kk = 0, id = 0;
+        const bool have = base + k < n_kind;
+        if (have) {
+          id = cand_list[off_kind + base + k];
+          r = id / G;
+          kk = id % G;
+          S::sched_pair(r, kk, a, b);
           if (kind == 0) {
             S::manifold_pp(E, a, f2i(E[L.n_verts + a]), b, f2i(E[L.n_verts + b]), prm.tie_eps, m);
           } else if (kind == 1) {
@@ -763,7 +782,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           const float vbx = E[L.vel_x + b], vby = E[L.vel_y + b], wb = E[L.omega + b];
           const float tx = -m.ny, ty = m.nx;
           float4 lam = make_float4(0.f, 0.f, 0.f, 0.f);
-          const unsigned pb = (prev_bits >> (2 * r)) & 3u;
+          const unsigned pb = pstate[kk * 16 + r];
           if (prm.warm_start && pb != 0u)
             lam = *reinterpret_cast<const float4*>(Rg + L.lambda + 4 * S::pair_index(a, b));
           float pen = 0.f;
@@ -793,62 +812,63 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           rc.corr = prm.beta * fmaxf(pen - prm.slop, 0.f) / (ima + imb);          // A.3.7
           if (idx < K::POOL) rec_store(to_lds(pool + idx * kRecW), rc);
           else rec_store(spill + (idx - K::POOL) * kRecW, rc);
-          table[r * G + k] = (unsigned char)idx;
-          my_rounds |= 1u << r;
-          new_bits |= ((unsigned)act0 | ((unsigned)act1 << 1)) << (2 * r);
+          table[id] = (unsigned char)idx;
         }
+        if (have) pstate[kk * 16 + r] = (unsigned char)((unsigned)act0 | ((unsigned)act1 << 1));
        }
       }
-      prev_bits = new_bits;
-      unsigned env_rounds = my_rounds;
-      for (int o = 1; o < G; o <<= 1) env_rounds |= __shfl_xor(env_rounds, o, G);
-      for (int i = k; i < N; i += G) blevel[i] = 0;
-      for (int i = k; i < R; i += G) lcount[i] = 0;
       __syncthreads();
-      // Dependency levels of the active pairs.  Walking the pairs in canonical order, a pair goes one
-      // level after the last earlier pair that shares a movable shape with it.  Pairs of one level touch
-      // disjoint movable shapes and pairs that share one keep their canonical order, so sweeping the
-      // levels in order, each level at once, gives the same bits as the sequential sweep -- in far fewer
-      // trips (everything resting on the static floor is one level; a level never exceeds the round).
-      for_each_round(env_rounds, my_rounds, [&](int r) {
-        int a, b;
-        S::sched_pair(r, k, a, b);
-        const bool da = !((static_mask >> a) & 1u), db = !((static_mask >> b) & 1u);
-        int lv = max(da ? (int)blevel[a] : 0, db ? (int)blevel[b] : 0);
-        if (da) blevel[a] = (unsigned char)(lv + 1);
-        if (db) blevel[b] = (unsigned char)(lv + 1);
-        lvl_of[r * G + k] = (unsigned char)lv;
-        slot_of[r * G + k] = (unsigned char)atomicAdd(&lcount[lv], 1);
-      });
-      // sizes and start offsets of the levels, 8 bits each
-      unsigned long long cnt_lo = 0ull, cnt_hi = 0ull, off_lo = 0ull, off_hi = 0ull;
+      // Dependency levels of the active pairs.  Walking the pairs in canonical order (= ascending id), a
+      // pair goes one level after the last earlier pair that shares a movable shape with it.  Pairs of
+      // one level touch disjoint movable shapes and pairs that share one keep their canonical order, so
+      // sweeping the levels in order, each level at once, gives the same bits as the sequential sweep --
+      // in far fewer trips (everything resting on the static floor is one level; a level never exceeds
+      // the round).  Every lane walks the whole table in registers (no barrier); lane s mod G writes
+      // entry s of a level.
+      unsigned long long cnt_lo = 0ull, cnt_hi = 0ull;   // pairs per level, 8 bits each
       int n_clevels = 0;
       {
-        int run = 0;
-        for (int lv = 0; lv < R; ++lv) {
-          int c = lcount[lv];
-          if (lv < 8) { cnt_lo |= (unsigned long long)c << (8 * lv); off_lo |= (unsigned long long)run << (8 * lv); }
-          else { cnt_hi |= (unsigned long long)c << (8 * (lv - 8)); off_hi |= (unsigned long long)run << (8 * (lv - 8)); }
-          run += c;
-          if (c > 0) n_clevels = lv + 1;
+        unsigned long long nxt = 0ull;                   // next free level of every shape, 4 bits each
+        for (int w4 = 0; w4 < K::TABLE_W; w4 += 4) {
+          const uint4 tw = *reinterpret_cast<const uint4*>(table + 4 * w4);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            unsigned word = j == 0 ? tw.x : j == 1 ? tw.y : j == 2 ? tw.z : tw.w;
+            if (word != 0xffffffffu) {
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const unsigned idx = (word >> (8 * q)) & 0xffu;
+                if (idx != 0xffu) {
+                  const int id = 4 * (w4 + j) + q;
+                  int a, b;
+                  S::sched_pair(id / G, id % G, a, b);
+                  const bool da = !((static_mask >> a) & 1u), db = !((static_mask >> b) & 1u);
+                  const int la = da ? (int)((nxt >> (4 * a)) & 15ull) : 0, lb = db ? (int)((nxt >> (4 * b)) & 15ull) : 0;
+                  const int lv = max(la, lb);
+                  if (da) nxt = (nxt & ~(15ull << (4 * a))) | ((unsigned long long)(lv + 1) << (4 * a));
+                  if (db) nxt = (nxt & ~(15ull << (4 * b))) | ((unsigned long long)(lv + 1) << (4 * b));
+                  int slot;
+                  if (lv < 8) { slot = (int)((cnt_lo >> (8 * lv)) & 255ull); cnt_lo += 1ull << (8 * lv); }
+                  else { slot = (int)((cnt_hi >> (8 * (lv - 8))) & 255ull); cnt_hi += 1ull << (8 * (lv - 8)); }
+                  if ((slot & (G - 1)) == k && slot < K::LCAP) sched[lv * K::LCAP + slot] = (unsigned char)idx;
+                  n_clevels = max(n_clevels, lv + 1);
+                }
+              }
+            }
+          }
         }
       }
       auto cnt_of = [&](int lv) { return (int)(((lv < 8) ? (cnt_lo >> (8 * lv)) : (cnt_hi >> (8 * (lv - 8)))) & 255ull); };
-      auto off_of = [&](int lv) { return (int)(((lv < 8) ? (off_lo >> (8 * lv)) : (off_hi >> (8 * (lv - 8)))) & 255ull); };
-      for (unsigned rm = my_rounds; rm != 0u; rm &= rm - 1u) {
-        int r = __ffs(rm) - 1;
-        sched[off_of(lvl_of[r * G + k]) + slot_of[r * G + k]] = table[r * G + k];
-      }
       int wave_clevels = 0;
       for (int lv = 1; lv <= R; ++lv)
         if (__any(n_clevels >= lv)) wave_clevels = lv;
       __syncthreads();
-      // every lane may now serve any pair: the lanes of the group take the entries of a level G at a time
+      // every lane may serve any pair: the lanes of the group take the entries of a level G at a time
       auto for_each_level = [&](auto&& f) {
         for (int lv = 0; lv < wave_clevels; ++lv) {
-          const int c = cnt_of(lv), o = off_of(lv);
+          const int c = cnt_of(lv);
           for (int base = 0; __any(base < c); base += G) {
-            if (base + k < c) f((int)sched[o + base + k]);
+            if (base + k < c) f((int)sched[lv * K::LCAP + base + k]);
             __syncthreads();
           }
         }
@@ -949,9 +969,19 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       for_each_level([&](int idx) {
         float nx, ny, corr;
         int ab;
-        if (idx < K::POOL) { LdsF rp = to_lds(pool + idx * kRecW); nx = rp[0]; ny = rp[1]; corr = rp[3]; ab = f2i(rp[4]); }
-        else { const float* rp = spill + (idx - K::POOL) * kRecW; nx = rp[0]; ny = rp[1]; corr = rp[3]; ab = f2i(rp[4]); }
+        float4 lam;
+        if (idx < K::POOL) {
+          LdsF rp = to_lds(pool + idx * kRecW);
+          nx = rp[0]; ny = rp[1]; corr = rp[3]; ab = f2i(rp[4]);
+          lam = make_float4(rp[13], rp[14], rp[23], rp[24]);
+        } else {
+          const float* rp = spill + (idx - K::POOL) * kRecW;
+          nx = rp[0]; ny = rp[1]; corr = rp[3]; ab = f2i(rp[4]);
+          lam = make_float4(rp[13], rp[14], rp[23], rp[24]);
+        }
         const int a = ab & 0xff, b = (ab >> 8) & 0xff;
+        // the pair's accumulated impulses wait in the HBM record for the next substep (A.7)
+        if (env_ok) *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(a, b)) = lam;
         const float ima = E[L.inv_mass + a], imb = E[L.inv_mass + b];
         if (!((static_mask >> a) & 1u)) {
           E[L.pos_x + a] = E[L.pos_x + a] - (ima * corr) * nx;
@@ -962,19 +992,6 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           E[L.pos_y + b] = E[L.pos_y + b] + (imb * corr) * ny;
         }
       });
-      // the owner of each active pair keeps its accumulated impulses in the HBM record for the next
-      // substep (only the owner ever reads or writes them there)
-      if (env_ok) {
-        for (unsigned rm = my_rounds; rm != 0u; rm &= rm - 1u) {
-          int r = __ffs(rm) - 1;
-          int idx = table[r * G + k];
-          int ab;
-          float4 lam;
-          if (idx < K::POOL) { LdsF rp = to_lds(pool + idx * kRecW); ab = f2i(rp[4]); lam = make_float4(rp[13], rp[14], rp[23], rp[24]); }
-          else { const float* rp = spill + (idx - K::POOL) * kRecW; ab = f2i(rp[4]); lam = make_float4(rp[13], rp[14], rp[23], rp[24]); }
-          *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(ab & 0xff, (ab >> 8) & 0xff)) = lam;
-        }
-      }
       for (int lv = 0; lv < wave_levels; ++lv) {
         if (k < J && j_live && j_level == lv) {
           float ca = E[K::X_COS + ja], sa = E[K::X_SIN + ja], cb = E[K::X_COS + jb], sb = E[K::X_SIN + jb];
@@ -1015,7 +1032,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
     unsigned char* ps = reinterpret_cast<unsigned char*>(Rg + L.pair_state);
     for (int r = 0; r < R; ++r) {
       int a, b;
-      if (S::sched_pair(r, k, a, b)) ps[S::pair_index(a, b)] = (unsigned char)((prev_bits >> (2 * r)) & 3u);
+      if (S::sched_pair(r, k, a, b)) ps[S::pair_index(a, b)] = pstate[k * 16 + r];
     }
   }
 }
@@ -1144,7 +1161,7 @@ __global__ void k2d_contacts_kernel(const float* state, uint8_t* pair_count, uin
 // ---------------------------------------------------------------------------------------------------
 using CfgS = Cfg<5, 2, 1, 1, 21>;
 using CfgM = Cfg<6, 3, 2, 2, 36>;
-using CfgL = Cfg<12, 4, 6, 2, 18>;
+using CfgL = Cfg<12, 4, 6, 2, 17>;
 // four L wavefronts must share one CU's 160 KiB of LDS: with 8192 environments every SIMD then holds one
 static_assert(CfgL::LDS_BYTES <= 40960, "L image too large for four wavefronts per CU");
 
