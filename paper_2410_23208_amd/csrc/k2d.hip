@@ -90,16 +90,19 @@ constexpr k2d_layout make_layout(int P, int C, int J, int T) {
 }
 
 // Compile-time description of one capacity class and of its LDS image.
-template <int P_, int C_, int J_, int T_, int POOL_>
+template <int P_, int C_, int J_, int T_, int POOL_, int H_>
 struct Cfg {
-  static constexpr int P = P_, C = C_, J = J_, T = T_, POOL = POOL_;
+  static constexpr int P = P_, C = C_, J = J_, T = T_, POOL = POOL_, H = H_;
   static constexpr int N = P + C, NP = N * (N - 1) / 2, A = J + T;
   static constexpr int M = N + (N & 1);   // tournament size (an odd N gets a phantom that sits out)
   static constexpr int R = M - 1;         // rounds
   static constexpr int PPR = M / 2;       // pairs per round
-  static constexpr int G = PPR <= 4 ? 4 : 8;   // lanes per environment
+  static constexpr int GP = PPR <= 4 ? 4 : 8;  // lanes that share the pairs of one round
+  static constexpr int G = GP * H;             // lanes per environment: lane k tests pair k % GP of the rounds
+                                               // r with r % H == k / GP
   static constexpr int EPW = 64 / G;           // environments per wavefront
-  static_assert(PPR <= 8 && J <= G && T <= G && N <= 2 * G && R <= 15, "capacity class does not fit the lane mapping");
+  static_assert(PPR <= 8 && J <= G && T <= G && R <= 15 && G <= 32 && (H & (H - 1)) == 0,
+                "capacity class does not fit the lane mapping");
   static constexpr k2d_layout L = make_layout(P, C, J, T);
   // HBM record: state words, then room for the pair records that do not fit the LDS pool
   static constexpr int SPILL = (NP > POOL ? NP - POOL : 0);
@@ -111,7 +114,7 @@ struct Cfg {
   static constexpr int X_BRAD = X_SIN + N;       // bounding radius of every shape
   static constexpr int X_WV = align_up(X_BRAD + N, 2);     // world vertices, float2 [4][P]
   static constexpr int X_WN = X_WV + 8 * P;                // outward unit edge normals, float2 [4][P]
-  static constexpr int NID = R * G;                        // pair ids: id = r * G + k (canonical order)
+  static constexpr int NID = R * GP;                       // pair ids: id = r * GP + k (canonical order)
   static constexpr int X_TABLE = align_up(X_WN + 8 * P, 4);        // bytes [NID]: pool index of pair id, 0xFF = none
   static constexpr int TABLE_W = align_up((NID + 3) / 4, 4);       // read back four words at a time
   static constexpr int X_LIST = X_TABLE + TABLE_W;         // bytes [NID]: candidate ids, one shape-type mix after the other
@@ -120,7 +123,7 @@ struct Cfg {
   static constexpr int LCAP = 16;                          // a level holds at most one pair per movable shape
   static constexpr int X_SCHED = X_LIST + LIST_W;          // bytes [R][LCAP]: pool indices, level by level
   static constexpr int X_PSTATE = align_up(X_SCHED + R * LCAP / 4, 4);   // bytes [G][16]: active-point bits of pair (r, k) at [k][r]
-  static constexpr int X_POOL = X_PSTATE + G * 4;
+  static constexpr int X_POOL = X_PSTATE + GP * 4;
   static constexpr int LDS_WORDS = X_POOL + POOL * kRecW;
   // stride = odd multiple of G words: the same word of different environments falls into different banks
   static constexpr int LDS_STRIDE = align_up(LDS_WORDS - G, 2 * G) + G;
@@ -458,11 +461,12 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
                                                       int n_envs, int n_steps, Params prm) {
   using S = Step<K>;
   constexpr k2d_layout L = K::L;
-  constexpr int N = K::N, P = K::P, J = K::J, T = K::T, G = K::G, R = K::R;
+  constexpr int N = K::N, P = K::P, J = K::J, T = K::T, G = K::G, R = K::R, GP = K::GP, H = K::H;
   extern __shared__ __align__(16) float lds[];
 
   const int lane = threadIdx.x;
   const int g = lane / G, k = lane % G;
+  const int kp = k % GP, rpar = k / GP;   // this lane's pair slot within a round, and which rounds it takes
   const int env0 = blockIdx.x * K::EPW;
   const int env = env0 + g;
   const bool env_ok = env < n_envs;
@@ -581,10 +585,15 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
   unsigned char* sched = reinterpret_cast<unsigned char*>(E + K::X_SCHED);
   unsigned char* pstate = reinterpret_cast<unsigned char*>(E + K::X_PSTATE);
   unsigned elig = 0u, pp_mask = 0u, pc_mask = 0u;
-  for (int r = 0; r < 16; ++r) pstate[k * 16 + r] = 0;
+  if (k < GP)
+    for (int r = 0; r < 16; ++r) pstate[k * 16 + r] = 0;
+  __syncthreads();
+  unsigned my_r = 0u;   // the rounds this lane takes
+  for (int r = 0; r < R; ++r)
+    if (r % H == rpar) my_r |= 1u << r;
   for (int r = 0; r < R; ++r) {
     int a, b;
-    if (S::sched_pair(r, k, a, b)) {
+    if (((my_r >> r) & 1u) && S::sched_pair(r, kp, a, b)) {
       if (b < P) pp_mask |= 1u << r;
       else if (a < P) pc_mask |= 1u << r;
       bool ok = (f2i(E[L.shape_flags + a]) & 1) && (f2i(E[L.shape_flags + b]) & 1) &&
@@ -593,7 +602,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         elig |= 1u << r;
         if (env_ok) {
           const unsigned char* ps = reinterpret_cast<const unsigned char*>(Rg + L.pair_state);
-          pstate[k * 16 + r] = ps[S::pair_index(a, b)] & 3;
+          pstate[kp * 16 + r] = ps[S::pair_index(a, b)] & 3;
         }
       }
     }
@@ -705,21 +714,21 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       for (int r = 0; r < R; ++r) {
         if ((elig >> r) & 1u) {
           int a, b;
-          S::sched_pair(r, k, a, b);
+          S::sched_pair(r, kp, a, b);
           float dx = E[L.pos_x + b] - E[L.pos_x + a], dy = E[L.pos_y + b] - E[L.pos_y + a];
           float rr = (E[K::X_BRAD + a] + E[K::X_BRAD + b]) * 1.0001f + 1e-5f;
           if (dx * dx + dy * dy <= rr * rr) cand |= 1u << r;
         }
       }
       {   // pairs that were colliding and are not even candidates now: their points are no longer active
-        uint4 ps = *reinterpret_cast<const uint4*>(pstate + k * 16);
+        uint4 ps = *reinterpret_cast<const uint4*>(pstate + kp * 16);
         unsigned nz = 0u;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
           unsigned w = r < 4 ? ps.x : r < 8 ? ps.y : r < 12 ? ps.z : ps.w;
           if ((w >> (8 * (r & 3))) & 0xffu) nz |= 1u << r;
         }
-        for (unsigned st = nz & ~cand; st != 0u; st &= st - 1u) pstate[k * 16 + (__ffs(st) - 1)] = 0;
+        for (unsigned st = nz & ~cand & my_r; st != 0u; st &= st - 1u) pstate[kp * 16 + (__ffs(st) - 1)] = 0;
       }
       for (int i = k; i < K::TABLE_W; i += G) reinterpret_cast<unsigned*>(table)[i] = 0xffffffffu;
       int kind_n[3], kind_off[3];
@@ -736,9 +745,9 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         kind_off[0] = 0; kind_off[1] = kind_n[0]; kind_off[2] = kind_n[0] + kind_n[1];
         int w0 = kind_off[0] + (int)(excl & 255), w1 = kind_off[1] + (int)((excl >> 8) & 255);
         int w2 = kind_off[2] + (int)((excl >> 16) & 255);
-        for (unsigned mm = m0; mm != 0u; mm &= mm - 1u) cand_list[w0++] = (unsigned char)((__ffs(mm) - 1) * G + k);
-        for (unsigned mm = m1; mm != 0u; mm &= mm - 1u) cand_list[w1++] = (unsigned char)((__ffs(mm) - 1) * G + k);
-        for (unsigned mm = m2; mm != 0u; mm &= mm - 1u) cand_list[w2++] = (unsigned char)((__ffs(mm) - 1) * G + k);
+        for (unsigned mm = m0; mm != 0u; mm &= mm - 1u) cand_list[w0++] = (unsigned char)((__ffs(mm) - 1) * GP + kp);
+        for (unsigned mm = m1; mm != 0u; mm &= mm - 1u) cand_list[w1++] = (unsigned char)((__ffs(mm) - 1) * GP + kp);
+        for (unsigned mm = m2; mm != 0u; mm &= mm - 1u) cand_list[w2++] = (unsigned char)((__ffs(mm) - 1) * GP + kp);
       }
       __syncthreads();
       int pool_base = 0;
@@ -750,8 +759,8 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         const bool have = base + k < n_kind;
         if (have) {
           id = cand_list[off_kind + base + k];
-          r = id / G;
-          kk = id % G;
+          r = id / GP;
+          kk = id % GP;
           S::sched_pair(r, kk, a, b);
           if (kind == 0) {
             S::manifold_pp(E, a, f2i(E[L.n_verts + a]), b, f2i(E[L.n_verts + b]), prm.tie_eps, m);
@@ -841,7 +850,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
                 if (idx != 0xffu) {
                   const int id = 4 * (w4 + j) + q;
                   int a, b;
-                  S::sched_pair(id / G, id % G, a, b);
+                  S::sched_pair(id / GP, id % GP, a, b);
                   const bool da = !((static_mask >> a) & 1u), db = !((static_mask >> b) & 1u);
                   const int la = da ? (int)((nxt >> (4 * a)) & 15ull) : 0, lb = db ? (int)((nxt >> (4 * b)) & 15ull) : 0;
                   const int lv = max(la, lb);
@@ -1032,7 +1041,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
     unsigned char* ps = reinterpret_cast<unsigned char*>(Rg + L.pair_state);
     for (int r = 0; r < R; ++r) {
       int a, b;
-      if (S::sched_pair(r, k, a, b)) ps[S::pair_index(a, b)] = pstate[k * 16 + r];
+      if (((my_r >> r) & 1u) && S::sched_pair(r, kp, a, b)) ps[S::pair_index(a, b)] = pstate[kp * 16 + r];
     }
   }
 }
@@ -1159,11 +1168,14 @@ __global__ void k2d_contacts_kernel(const float* state, uint8_t* pair_count, uin
 // ---------------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------------
-using CfgS = Cfg<5, 2, 1, 1, 21>;
-using CfgM = Cfg<6, 3, 2, 2, 36>;
-using CfgL = Cfg<12, 4, 6, 2, 17>;
+#ifndef K2D_H_L
+#define K2D_H_L 2
+#endif
+using CfgS = Cfg<5, 2, 1, 1, 21, 4>;
+using CfgM = Cfg<6, 3, 2, 2, 36, 2>;
+using CfgL = Cfg<12, 4, 6, 2, 17, K2D_H_L>;
 // four L wavefronts must share one CU's 160 KiB of LDS: with 8192 environments every SIMD then holds one
-static_assert(CfgL::LDS_BYTES <= 40960, "L image too large for four wavefronts per CU");
+static_assert(CfgL::LDS_BYTES * CfgL::G <= 40960 * 8, "L image too large: every SIMD must be able to hold 16 L environments' worth of lanes");
 
 int caps_class(const k2d_caps* c) {
   if (!c) return -1;
