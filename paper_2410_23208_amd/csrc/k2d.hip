@@ -774,7 +774,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         const bool act0 = m.valid[0] && m.pen[0] > 0.f, act1 = m.valid[1] && m.pen[1] > 0.f;
         const bool active = act0 || act1;
         unsigned long long bal = __ballot(active);
-        unsigned envbits = (unsigned)(bal >> (g * G)) & ((1u << G) - 1u);
+        unsigned envbits = (unsigned)(bal >> (g * G)) & (G >= 32 ? 0xffffffffu : ((1u << (G & 31)) - 1u));
         int idx = pool_base + __popc(envbits & ((1u << k) - 1u));
         pool_base += __popc(envbits);
         if (active) {
