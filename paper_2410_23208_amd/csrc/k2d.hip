@@ -123,7 +123,8 @@ struct Cfg {
   static constexpr int LCAP = 16;                          // a level holds at most one pair per movable shape
   static constexpr int X_SCHED = X_LIST + LIST_W;          // bytes [R][LCAP]: pool indices, level by level
   static constexpr int X_PSTATE = align_up(X_SCHED + R * LCAP / 4, 4);   // bytes [G][16]: active-point bits of pair (r, k) at [k][r]
-  static constexpr int X_POOL = X_PSTATE + GP * 4;
+  static constexpr int X_BITMAP = X_PSTATE + GP * 4;       // 4 words: bit id set = pair id is active this substep
+  static constexpr int X_POOL = X_BITMAP + 4;
   static constexpr int LDS_WORDS = X_POOL + POOL * kRecW;
   // stride = odd multiple of G words: the same word of different environments falls into different banks
   static constexpr int LDS_STRIDE = align_up(LDS_WORDS - G, 2 * G) + G;
@@ -584,6 +585,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
   unsigned char* cand_list = reinterpret_cast<unsigned char*>(E + K::X_LIST);
   unsigned char* sched = reinterpret_cast<unsigned char*>(E + K::X_SCHED);
   unsigned char* pstate = reinterpret_cast<unsigned char*>(E + K::X_PSTATE);
+  unsigned* bitmap = reinterpret_cast<unsigned*>(E + K::X_BITMAP);
   unsigned elig = 0u, pp_mask = 0u, pc_mask = 0u;
   if (k < GP)
     for (int r = 0; r < 16; ++r) pstate[k * 16 + r] = 0;
@@ -730,7 +732,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         }
         for (unsigned st = nz & ~cand & my_r; st != 0u; st &= st - 1u) pstate[kp * 16 + (__ffs(st) - 1)] = 0;
       }
-      for (int i = k; i < K::TABLE_W; i += G) reinterpret_cast<unsigned*>(table)[i] = 0xffffffffu;
+      if (k < 4) bitmap[k] = 0u;
       int kind_n[3], kind_off[3];
       {
         const unsigned m0 = cand & pp_mask, m1 = cand & pc_mask, m2 = cand & ~(pp_mask | pc_mask);
@@ -822,6 +824,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           if (idx < K::POOL) rec_store(to_lds(pool + idx * kRecW), rc);
           else rec_store(spill + (idx - K::POOL) * kRecW, rc);
           table[id] = (unsigned char)idx;
+          atomicOr(&bitmap[id >> 5], 1u << (id & 31));
         }
         if (have) pstate[kk * 16 + r] = (unsigned char)((unsigned)act0 | ((unsigned)act1 << 1));
        }
@@ -834,40 +837,30 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       // in far fewer trips (everything resting on the static floor is one level; a level never exceeds
       // the round).  Every lane walks the whole table in registers (no barrier); lane s mod G writes
       // entry s of a level.
-      unsigned long long cnt_lo = 0ull, cnt_hi = 0ull;   // pairs per level, 8 bits each
+      unsigned long long level_cnt = 0ull;   // pairs per level, 4 bits each (a level holds fewer than 16)
       int n_clevels = 0;
       {
-        unsigned long long nxt = 0ull;                   // next free level of every shape, 4 bits each
-        for (int w4 = 0; w4 < K::TABLE_W; w4 += 4) {
-          const uint4 tw = *reinterpret_cast<const uint4*>(table + 4 * w4);
+        unsigned long long nxt = 0ull;       // next free level of every shape, 4 bits each
+        const uint4 bm = *reinterpret_cast<const uint4*>(bitmap);
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            unsigned word = j == 0 ? tw.x : j == 1 ? tw.y : j == 2 ? tw.z : tw.w;
-            if (word != 0xffffffffu) {
-#pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                const unsigned idx = (word >> (8 * q)) & 0xffu;
-                if (idx != 0xffu) {
-                  const int id = 4 * (w4 + j) + q;
-                  int a, b;
-                  S::sched_pair(id / GP, id % GP, a, b);
-                  const bool da = !((static_mask >> a) & 1u), db = !((static_mask >> b) & 1u);
-                  const int la = da ? (int)((nxt >> (4 * a)) & 15ull) : 0, lb = db ? (int)((nxt >> (4 * b)) & 15ull) : 0;
-                  const int lv = max(la, lb);
-                  if (da) nxt = (nxt & ~(15ull << (4 * a))) | ((unsigned long long)(lv + 1) << (4 * a));
-                  if (db) nxt = (nxt & ~(15ull << (4 * b))) | ((unsigned long long)(lv + 1) << (4 * b));
-                  int slot;
-                  if (lv < 8) { slot = (int)((cnt_lo >> (8 * lv)) & 255ull); cnt_lo += 1ull << (8 * lv); }
-                  else { slot = (int)((cnt_hi >> (8 * (lv - 8))) & 255ull); cnt_hi += 1ull << (8 * (lv - 8)); }
-                  if ((slot & (G - 1)) == k && slot < K::LCAP) sched[lv * K::LCAP + slot] = (unsigned char)idx;
-                  n_clevels = max(n_clevels, lv + 1);
-                }
-              }
-            }
+        for (int w = 0; w < 4; ++w) {
+          for (unsigned bits = w == 0 ? bm.x : w == 1 ? bm.y : w == 2 ? bm.z : bm.w; bits != 0u; bits &= bits - 1u) {
+            const int id = 32 * w + __ffs(bits) - 1;
+            int a, b;
+            S::sched_pair(id / GP, id % GP, a, b);
+            const bool da = !((static_mask >> a) & 1u), db = !((static_mask >> b) & 1u);
+            const int la = da ? (int)((nxt >> (4 * a)) & 15ull) : 0, lb = db ? (int)((nxt >> (4 * b)) & 15ull) : 0;
+            const int lv = max(la, lb);
+            if (da) nxt = (nxt & ~(15ull << (4 * a))) | ((unsigned long long)(lv + 1) << (4 * a));
+            if (db) nxt = (nxt & ~(15ull << (4 * b))) | ((unsigned long long)(lv + 1) << (4 * b));
+            const int slot = (int)((level_cnt >> (4 * lv)) & 15ull);
+            level_cnt += 1ull << (4 * lv);
+            if ((slot & (G - 1)) == k) sched[lv * K::LCAP + slot] = table[id];
+            n_clevels = max(n_clevels, lv + 1);
           }
         }
       }
-      auto cnt_of = [&](int lv) { return (int)(((lv < 8) ? (cnt_lo >> (8 * lv)) : (cnt_hi >> (8 * (lv - 8)))) & 255ull); };
+      auto cnt_of = [&](int lv) { return (int)((level_cnt >> (4 * lv)) & 15ull); };
       int wave_clevels = 0;
       for (int lv = 1; lv <= R; ++lv)
         if (__any(n_clevels >= lv)) wave_clevels = lv;
