@@ -65,11 +65,16 @@ struct V2 {
 template <class R> inline V2<R> operator+(V2<R> a, V2<R> b) { return {a.x + b.x, a.y + b.y}; }
 template <class R> inline V2<R> operator-(V2<R> a, V2<R> b) { return {a.x - b.x, a.y - b.y}; }
 template <class R> inline V2<R> operator*(R s, V2<R> a) { return {s * a.x, s * a.y}; }
-template <class R> inline R dot(V2<R> a, V2<R> b) { return a.x * b.x + a.y * b.y; }
+// The two-term products below (dot, cross, rotation, "v + s*j") round once: they are written with the
+// fused multiply-add every current CPU and GPU has, p*q + r*s = fma(p, q, r*s).  Everything else in this
+// file is plain one-operation-one-rounding arithmetic (the build switches contraction off).
+template <class R> inline R dot(V2<R> a, V2<R> b) { return std::fma(a.x, b.x, a.y * b.y); }
 // vector x vector -> scalar, scalar x vector -> vector (A.2: "the choice should be inferable")
-template <class R> inline R cross(V2<R> a, V2<R> b) { return a.x * b.y - a.y * b.x; }
+template <class R> inline R cross(V2<R> a, V2<R> b) { return std::fma(a.x, b.y, -(a.y * b.x)); }
 template <class R> inline V2<R> cross(R w, V2<R> r) { return {-w * r.y, w * r.x}; }
-template <class R> inline V2<R> rotate(R c, R s, V2<R> l) { return {c * l.x - s * l.y, s * l.x + c * l.y}; }
+template <class R> inline V2<R> rotate(R c, R s, V2<R> l) { return {std::fma(c, l.x, -(s * l.y)), std::fma(s, l.x, c * l.y)}; }
+// v + s*j
+template <class R> inline V2<R> madd(V2<R> v, R s, V2<R> j) { return {std::fma(s, j.x, v.x), std::fma(s, j.y, v.y)}; }
 
 // ----------------------------------------------------------------------------------------------
 // sin, cos and tanh.  In double they are libm's.  In fp32 -- the engine's precision -- they are fixed
@@ -381,14 +386,16 @@ void manifold_pp(const WorldPoly<R>& A, const WorldPoly<R>& B, R tie_eps, Manifo
 // ----------------------------------------------------------------------------------------------
 template <class R>
 inline void apply_impulse(Body<R>& b, V2<R> j, V2<R> r) {
-  b.vel = b.vel + b.inv_mass * j;
-  b.omega = b.omega + b.inv_inertia * cross(r, j);
+  b.vel = madd(b.vel, b.inv_mass, j);
+  b.omega = std::fma(b.inv_inertia, cross(r, j), b.omega);
 }
 
 // Relative velocity of the contact points: v_a + w_a x r_a - v_b - w_b x r_b (A.3.5).
 template <class R>
 inline V2<R> rel_vel(const Body<R>& a, V2<R> ra, const Body<R>& b, V2<R> rb) {
-  return a.vel + cross(a.omega, ra) - b.vel - cross(b.omega, rb);
+  // with w x r = (-w r_y, w r_x), one fused multiply-add per cross term
+  return {std::fma(b.omega, rb.y, std::fma(-a.omega, ra.y, a.vel.x) - b.vel.x),
+          std::fma(-b.omega, rb.x, std::fma(a.omega, ra.x, a.vel.y) - b.vel.y)};
 }
 
 template <class R>

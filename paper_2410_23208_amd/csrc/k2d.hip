@@ -23,7 +23,8 @@
 //     independent, so they are grouped into dependency levels once per launch and lane j solves joint j.
 //
 // Nothing here is a dense contraction: no MFMA.  Arithmetic is fp32; the kernel is compiled without
-// contraction of a*b+c so that it rounds like a plain evaluation of the formulas.
+// automatic contraction of a*b+c; the fused multiply-adds are the ones written out (dot and cross
+// products, rotations, impulse application), so the rounding of every formula is fixed by the source.
 
 #include <hip/hip_runtime.h>
 
@@ -183,6 +184,18 @@ __device__ __forceinline__ float k2d_tanh(float x) {
 }
 __device__ __forceinline__ float i2f(int i) { return __int_as_float(i); }
 
+// Two-term products round once: a.b = fma(ax, bx, ay*by), a x b = fma(ax, by, -(ay*bx)); an impulse is
+// applied as v = fma(1/m, j, v).  Everything else is one operation, one rounding (contraction is off).
+__device__ __forceinline__ float dot2(float ax, float ay, float bx, float by) { return fmaf(ax, bx, ay * by); }
+__device__ __forceinline__ float cross2(float ax, float ay, float bx, float by) { return fmaf(ax, by, -(ay * bx)); }
+// an impulse (jx, jy) at offset (rx, ry) from the centre of mass (A.2)
+__device__ __forceinline__ void apply_impulse(float& vx, float& vy, float& w, float im, float ii, float jx, float jy,
+                                              float rx, float ry) {
+  vx = fmaf(im, jx, vx);
+  vy = fmaf(im, jy, vy);
+  w = fmaf(ii, cross2(rx, ry, jx, jy), w);
+}
+
 // One active pair of the current substep.  Body indices and per-point activity are packed in `ab`.
 struct PairRec {
   float nx, ny, mu, corr;        // unit normal a->b; friction coefficient; positional-correction length
@@ -259,7 +272,7 @@ struct Step {
   static __device__ __forceinline__ void manifold_cc(float pax, float pay, float ra, float pbx, float pby, float rb,
                                                      Manifold& m) {
     float dx = pbx - pax, dy = pby - pay;
-    float len = sqrtf(dx * dx + dy * dy);
+    float len = sqrtf(dot2(dx, dy, dx, dy));
     bool ok = len > 1e-9f;
     m.nx = ok ? dx / len : 1.f;
     m.ny = ok ? dy / len : 0.f;
@@ -283,13 +296,13 @@ struct Step {
         float2 nr = wn(E, i, pa);
         float ex = v1.x - v.x, ey = v1.y - v.y;
         float rx = cx - v.x, ry = cy - v.y;
-        float t = (rx * ex + ry * ey) / (ex * ex + ey * ey);
+        float t = dot2(rx, ry, ex, ey) / dot2(ex, ey, ex, ey);
         t = fminf(fmaxf(t, 0.f), 1.f);
         float qix = v.x + t * ex, qiy = v.y + t * ey;
         float dqx = cx - qix, dqy = cy - qiy;
-        float d2 = dqx * dqx + dqy * dqy;
+        float d2 = dot2(dqx, dqy, dqx, dqy);
         if (d2 < best_d2) { best_d2 = d2; qx = qix; qy = qiy; }
-        float s = nr.x * rx + nr.y * ry;
+        float s = dot2(nr.x, nr.y, rx, ry);
         if (s > smax) { smax = s; snx = nr.x; sny = nr.y; }
         v = v1;
       }
@@ -323,7 +336,7 @@ struct Step {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           if (k < ny_) {
-            float s = nr.x * (yw[k].x - w.x) + nr.y * (yw[k].y - w.y);
+            float s = dot2(nr.x, nr.y, yw[k].x - w.x, yw[k].y - w.y);
             smin = (s < smin) ? s : smin;
           }
         }
@@ -355,16 +368,16 @@ struct Step {
     for (int j = 0; j < 4; ++j) {
       if (j < ni) {
         float2 nj = wn(E, j, pi);
-        float d = nj.x * nref.x + nj.y * nref.y;
+        float d = dot2(nj.x, nj.y, nref.x, nref.y);
         if (d < dmin) { dmin = d; jinc = j; }
       }
     }
     float2 v0 = wv(E, jinc, pi);
     float2 v1 = wv(E, (jinc + 1 == ni) ? 0 : jinc + 1, pi);
     float tx = -nref.y, ty = nref.x;
-    float u0 = tx * (v0.x - r1.x) + ty * (v0.y - r1.y);
-    float u1 = tx * (v1.x - r1.x) + ty * (v1.y - r1.y);
-    float len = tx * (r2.x - r1.x) + ty * (r2.y - r1.y);
+    float u0 = dot2(tx, ty, v0.x - r1.x, v0.y - r1.y);
+    float u1 = dot2(tx, ty, v1.x - r1.x, v1.y - r1.y);
+    float len = dot2(tx, ty, r2.x - r1.x, r2.y - r1.y);
     if ((u0 < 0.f && u1 < 0.f) || (u0 > len && u1 > len)) return;
     m.nx = ref_b ? -nref.x : nref.x;
     m.ny = ref_b ? -nref.y : nref.y;
@@ -379,7 +392,7 @@ struct Step {
         y = v0.y + s * (v1.y - v0.y);
       }
       m.px[k] = x; m.py[k] = y;
-      m.pen[k] = -(nref.x * (x - r1.x) + nref.y * (y - r1.y));
+      m.pen[k] = -dot2(nref.x, nref.y, x - r1.x, y - r1.y);
       m.valid[k] = true;
     }
   }
@@ -387,8 +400,8 @@ struct Step {
   // Relative velocity of the contact points, v_a + w_a x r_a - v_b - w_b x r_b (A.3.5).
   static __device__ __forceinline__ void rel_vel(float vax, float vay, float wa, float rax, float ray, float vbx,
                                                  float vby, float wb, float rbx, float rby, float& x, float& y) {
-    x = vax + (-wa * ray) - vbx - (-wb * rby);
-    y = vay + (wa * rax) - vby - (wb * rbx);
+    x = fmaf(wb, rby, fmaf(-wa, ray, vax) - vbx);
+    y = fmaf(-wb, rbx, fmaf(wa, rax, vay) - vby);
   }
 
   // One visit of an active pair in a solver sweep: per point, normal impulse then friction impulse,
@@ -405,28 +418,24 @@ struct Step {
       if ((rc.ab >> (16 + k)) & 1) {
         float rx, ry;
         rel_vel(vax, vay, wa, rc.rax[k], rc.ray[k], vbx, vby, wb, rc.rbx[k], rc.rby[k], rx, ry);
-        float vn = rc.nx * rx + rc.ny * ry;
+        float vn = dot2(rc.nx, rc.ny, rx, ry);
         float dl = rc.mass_n[k] * (vn + rc.rest[k] + rc.bias[k]);
         float ln = fmaxf(rc.lam_n[k] + dl, 0.f);
         dl = ln - rc.lam_n[k];
         rc.lam_n[k] = ln;
         float jx = (-dl) * rc.nx, jy = (-dl) * rc.ny;
-        vax = vax + ima * jx; vay = vay + ima * jy;
-        wa = wa + iia * (rc.rax[k] * jy - rc.ray[k] * jx);
-        vbx = vbx + imb * (-jx); vby = vby + imb * (-jy);
-        wb = wb + iib * (rc.rbx[k] * (-jy) - rc.rby[k] * (-jx));
+        apply_impulse(vax, vay, wa, ima, iia, jx, jy, rc.rax[k], rc.ray[k]);
+        apply_impulse(vbx, vby, wb, imb, iib, -jx, -jy, rc.rbx[k], rc.rby[k]);
         rel_vel(vax, vay, wa, rc.rax[k], rc.ray[k], vbx, vby, wb, rc.rbx[k], rc.rby[k], rx, ry);
-        float vt = tx * rx + ty * ry;
+        float vt = dot2(tx, ty, rx, ry);
         float dt_ = -rc.mass_t[k] * vt;
         float lim = rc.mu * ln;
         float lt = fminf(fmaxf(rc.lam_t[k] + dt_, -lim), lim);
         dt_ = lt - rc.lam_t[k];
         rc.lam_t[k] = lt;
         float fx = dt_ * tx, fy = dt_ * ty;
-        vax = vax + ima * fx; vay = vay + ima * fy;
-        wa = wa + iia * (rc.rax[k] * fy - rc.ray[k] * fx);
-        vbx = vbx + imb * (-fx); vby = vby + imb * (-fy);
-        wb = wb + iib * (rc.rbx[k] * (-fy) - rc.rby[k] * (-fx));
+        apply_impulse(vax, vay, wa, ima, iia, fx, fy, rc.rax[k], rc.ray[k]);
+        apply_impulse(vbx, vby, wb, imb, iib, -fx, -fy, rc.rbx[k], rc.rby[k]);
       }
     }
     if (!((fixed >> a) & 1u)) { E[L.vel_x + a] = vax; E[L.vel_y + a] = vay; E[L.omega + a] = wa; }
@@ -446,10 +455,8 @@ struct Step {
       if ((rc.ab >> (16 + k)) & 1) {
         float jx = (-rc.lam_n[k]) * rc.nx + rc.lam_t[k] * tx;
         float jy = (-rc.lam_n[k]) * rc.ny + rc.lam_t[k] * ty;
-        vax = vax + ima * jx; vay = vay + ima * jy;
-        wa = wa + iia * (rc.rax[k] * jy - rc.ray[k] * jx);
-        vbx = vbx + imb * (-jx); vby = vby + imb * (-jy);
-        wb = wb + iib * (rc.rbx[k] * (-jy) - rc.rby[k] * (-jx));
+        apply_impulse(vax, vay, wa, ima, iia, jx, jy, rc.rax[k], rc.ray[k]);
+        apply_impulse(vbx, vby, wb, imb, iib, -jx, -jy, rc.rbx[k], rc.rby[k]);
       }
     }
     if (!((fixed >> a) & 1u)) { E[L.vel_x + a] = vax; E[L.vel_y + a] = vay; E[L.omega + a] = wa; }
@@ -636,14 +643,14 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             float lx = E[L.verts + (2 * v) * P + i], ly = E[L.verts + (2 * v + 1) * P + i];
-            wx[v] = px + (cs * lx - sn * ly);
-            wy[v] = py + (sn * lx + cs * ly);
+            wx[v] = px + fmaf(cs, lx, -(sn * ly));
+            wy[v] = py + fmaf(sn, lx, cs * ly);
           }
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             int v1 = (v + 1 == nv) ? 0 : ((v + 1) & 3);
             float ex = wx[v1] - wx[v], ey = wy[v1] - wy[v];
-            float len = sqrtf(ex * ex + ey * ey);
+            float len = sqrtf(dot2(ex, ey, ex, ey));
             *reinterpret_cast<float2*>(E + K::X_WV + 2 * (v * P + i)) = make_float2(wx[v], wy[v]);
             *reinterpret_cast<float2*>(E + K::X_WN + 2 * (v * P + i)) = make_float2(ey / len, -ex / len);
           }
@@ -660,8 +667,8 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         j_ima = E[L.inv_mass + ja]; j_iia = E[L.inv_inertia + ja];
         j_imb = E[L.inv_mass + jb]; j_iib = E[L.inv_inertia + jb];
         float ca = E[K::X_COS + ja], sa = E[K::X_SIN + ja], cb = E[K::X_COS + jb], sb = E[K::X_SIN + jb];
-        j_rax = ca * j_aax - sa * j_aay; j_ray = sa * j_aax + ca * j_aay;
-        j_rbx = cb * j_abx - sb * j_aby; j_rby = sb * j_abx + cb * j_aby;
+        j_rax = fmaf(ca, j_aax, -(sa * j_aay)); j_ray = fmaf(sa, j_aax, ca * j_aay);
+        j_rbx = fmaf(cb, j_abx, -(sb * j_aby)); j_rby = fmaf(sb, j_abx, cb * j_aby);
         float ms = j_ima + j_imb;
         j_k11 = ms + j_iia * j_ray * j_ray + j_iib * j_rby * j_rby;
         j_k22 = ms + j_iia * j_rax * j_rax + j_iib * j_rbx * j_rbx;
@@ -681,8 +688,8 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       float t_ix = 0.f, t_iy = 0.f, t_rx = 0.f, t_ry = 0.f;
       if (k < T && t_live) {   // A.6
         float cs = E[K::X_COS + t_body], sn = E[K::X_SIN + t_body];
-        float dx = cs * t_dx - sn * t_dy, dy = sn * t_dx + cs * t_dy;
-        t_rx = cs * t_px - sn * t_py; t_ry = sn * t_px + cs * t_py;
+        float dx = fmaf(cs, t_dx, -(sn * t_dy)), dy = fmaf(sn, t_dx, cs * t_dy);
+        t_rx = fmaf(cs, t_px, -(sn * t_py)); t_ry = fmaf(sn, t_px, cs * t_py);
         float f = t_power * act_t * h;
         t_ix = f * dx; t_iy = f * dy;
       }
@@ -697,9 +704,9 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       for (int t = 0; t < T; ++t) {
         if (k == t && t_live) {
           float im = E[L.inv_mass + t_body], ii = E[L.inv_inertia + t_body];
-          E[L.vel_x + t_body] = E[L.vel_x + t_body] + im * t_ix;
-          E[L.vel_y + t_body] = E[L.vel_y + t_body] + im * t_iy;
-          E[L.omega + t_body] = E[L.omega + t_body] + ii * (t_rx * t_iy - t_ry * t_ix);
+          E[L.vel_x + t_body] = fmaf(im, t_ix, E[L.vel_x + t_body]);
+          E[L.vel_y + t_body] = fmaf(im, t_iy, E[L.vel_y + t_body]);
+          E[L.omega + t_body] = fmaf(ii, cross2(t_rx, t_ry, t_ix, t_iy), E[L.omega + t_body]);
         }
         __syncthreads();
       }
@@ -802,8 +809,8 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
             const bool on = q ? act1 : act0;
             rc.rax[q] = m.px[q] - pax; rc.ray[q] = m.py[q] - pay;
             rc.rbx[q] = m.px[q] - pbx; rc.rby[q] = m.py[q] - pby;
-            float ran = rc.rax[q] * m.ny - rc.ray[q] * m.nx, rbn = rc.rbx[q] * m.ny - rc.rby[q] * m.nx;
-            float rat = rc.rax[q] * ty - rc.ray[q] * tx, rbt = rc.rbx[q] * ty - rc.rby[q] * tx;
+            float ran = cross2(rc.rax[q], rc.ray[q], m.nx, m.ny), rbn = cross2(rc.rbx[q], rc.rby[q], m.nx, m.ny);
+            float rat = cross2(rc.rax[q], rc.ray[q], tx, ty), rbt = cross2(rc.rbx[q], rc.rby[q], tx, ty);
             float kn = ima + imb + ran * ran * iia + rbn * rbn * iib;
             float kt = ima + imb + rat * rat * iia + rbt * rbt * iib;
             rc.mass_n[q] = on ? 1.f / kn : 0.f;
@@ -813,7 +820,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
             // before any constraint impulse; slow approaches take e = 0
             float rx, ry;
             S::rel_vel(vax, vay, wa, rc.rax[q], rc.ray[q], vbx, vby, wb, rc.rbx[q], rc.rby[q], rx, ry);
-            float vn0 = m.nx * rx + m.ny * ry;
+            float vn0 = dot2(m.nx, m.ny, rx, ry);
             rc.rest[q] = (vn0 > prm.rest_thr) ? e * vn0 : 0.f;
             bool keep = prm.warm_start && on && ((pb >> q) & 1u);                 // A.7
             rc.lam_n[q] = keep ? (q ? lam.z : lam.x) : 0.f;
@@ -892,14 +899,14 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
               wb = wb - j_iib * j_acca;
             }
             if (!ja_fix) {
-              E[L.vel_x + ja] = E[L.vel_x + ja] + j_ima * j_accx;
-              E[L.vel_y + ja] = E[L.vel_y + ja] + j_ima * j_accy;
-              E[L.omega + ja] = wa + j_iia * (j_rax * j_accy - j_ray * j_accx);
+              E[L.vel_x + ja] = fmaf(j_ima, j_accx, E[L.vel_x + ja]);
+              E[L.vel_y + ja] = fmaf(j_ima, j_accy, E[L.vel_y + ja]);
+              E[L.omega + ja] = fmaf(j_iia, cross2(j_rax, j_ray, j_accx, j_accy), wa);
             }
             if (!jb_fix) {
-              E[L.vel_x + jb] = E[L.vel_x + jb] + j_imb * (-j_accx);
-              E[L.vel_y + jb] = E[L.vel_y + jb] + j_imb * (-j_accy);
-              E[L.omega + jb] = wb + j_iib * (j_rbx * (-j_accy) - j_rby * (-j_accx));
+              E[L.vel_x + jb] = fmaf(j_imb, -j_accx, E[L.vel_x + jb]);
+              E[L.vel_y + jb] = fmaf(j_imb, -j_accy, E[L.vel_y + jb]);
+              E[L.omega + jb] = fmaf(j_iib, cross2(j_rbx, j_rby, -j_accx, -j_accy), wb);
             }
           }
           __syncthreads();
@@ -922,10 +929,8 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
             S::rel_vel(vax, vay, wa, j_rax, j_ray, vbx, vby, wb, j_rbx, j_rby, cx, cy);
             float rx = -(cx + j_bx), ry = -(cy + j_by);
             float jx = (j_k22 * rx - j_k12 * ry) * j_idet, jy = (j_k11 * ry - j_k12 * rx) * j_idet;
-            vax = vax + j_ima * jx; vay = vay + j_ima * jy;
-            wa = wa + j_iia * (j_rax * jy - j_ray * jx);
-            vbx = vbx + j_imb * (-jx); vby = vby + j_imb * (-jy);
-            wb = wb + j_iib * (j_rbx * (-jy) - j_rby * (-jx));
+            apply_impulse(vax, vay, wa, j_ima, j_iia, jx, jy, j_rax, j_ray);
+            apply_impulse(vbx, vby, wb, j_imb, j_iib, -jx, -jy, j_rbx, j_rby);
             j_accx = j_accx + jx; j_accy = j_accy + jy;
             if (!ja_fix) { E[L.vel_x + ja] = vax; E[L.vel_y + ja] = vay; E[L.omega + ja] = wa; }
             if (!jb_fix) { E[L.vel_x + jb] = vbx; E[L.vel_y + jb] = vby; E[L.omega + jb] = wb; }
@@ -997,8 +1002,8 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       for (int lv = 0; lv < wave_levels; ++lv) {
         if (k < J && j_live && j_level == lv) {
           float ca = E[K::X_COS + ja], sa = E[K::X_SIN + ja], cb = E[K::X_COS + jb], sb = E[K::X_SIN + jb];
-          float xax = E[L.pos_x + ja] + (ca * j_aax - sa * j_aay), xay = E[L.pos_y + ja] + (sa * j_aax + ca * j_aay);
-          float xbx = E[L.pos_x + jb] + (cb * j_abx - sb * j_aby), xby = E[L.pos_y + jb] + (sb * j_abx + cb * j_aby);
+          float xax = E[L.pos_x + ja] + fmaf(ca, j_aax, -(sa * j_aay)), xay = E[L.pos_y + ja] + fmaf(sa, j_aax, ca * j_aay);
+          float xbx = E[L.pos_x + jb] + fmaf(cb, j_abx, -(sb * j_aby)), xby = E[L.pos_y + jb] + fmaf(sb, j_abx, cb * j_aby);
           float cf = prm.joint_beta / (j_ima + j_imb);
           float cx = cf * (xax - xbx), cy = cf * (xay - xby);
           if (!ja_fix) {
