@@ -17,8 +17,10 @@
 //     parallel and is bit-identical to the sequential Gauss-Seidel sweep in that order (the sequential
 //     end of the speed/stability trade-off of A.8, reached without the paper's batch-of-16 compromise).
 //     Each environment walks only its own non-empty rounds.
-//   * Active manifolds of a substep are kept as records in a small LDS pool per environment; the rare
-//     environment with more active pairs than the pool holds spills the excess records to its HBM record.
+//   * Active manifolds of a substep become records that live in registers: lane k of the environment
+//     keeps active pairs k and G + k for the whole substep (warm start, all sweeps, corrections), so a
+//     visit costs one LDS round trip for the two bodies' velocities and nothing else.  Pairs beyond 2G
+//     stay in a small LDS pool, the rare excess beyond that spills to the environment's HBM record.
 //   * Joints are solved in index order per shape (A.8: sequential); joints that share no shape are
 //     independent, so they are grouped into dependency levels once per launch and lane j solves joint j.
 //
@@ -91,9 +93,9 @@ constexpr k2d_layout make_layout(int P, int C, int J, int T) {
 }
 
 // Compile-time description of one capacity class and of its LDS image.
-template <int P_, int C_, int J_, int T_, int POOL_, int H_>
+template <int P_, int C_, int J_, int T_, int H_>
 struct Cfg {
-  static constexpr int P = P_, C = C_, J = J_, T = T_, POOL = POOL_, H = H_;
+  static constexpr int P = P_, C = C_, J = J_, T = T_, H = H_;
   static constexpr int N = P + C, NP = N * (N - 1) / 2, A = J + T;
   static constexpr int M = N + (N & 1);   // tournament size (an odd N gets a phantom that sits out)
   static constexpr int R = M - 1;         // rounds
@@ -102,11 +104,16 @@ struct Cfg {
   static constexpr int G = GP * H;             // lanes per environment: lane k tests pair k % GP of the rounds
                                                // r with r % H == k / GP
   static constexpr int EPW = 64 / G;           // environments per wavefront
-  static_assert(PPR <= 8 && J <= G && T <= G && R <= 15 && G <= 32 && (H & (H - 1)) == 0,
+  static_assert(PPR <= 8 && J <= G && T <= G && R <= 15 && G == 16 && (H & (H - 1)) == 0,
                 "capacity class does not fit the lane mapping");
+  // Active pairs are numbered 0, 1, ... as the narrowphase finds them.  Pairs below NREG live in
+  // registers (lane k holds pairs k and G + k), the next POOL in LDS, the rest in the HBM record.  The
+  // POOL slots also stage the hand-over of a register-held record from the lane that computed it to the
+  // lane that keeps it: pair idx always uses slot idx % G.
+  static constexpr int NREG = 2 * G, POOL = G;
   static constexpr k2d_layout L = make_layout(P, C, J, T);
   // HBM record: state words, then room for the pair records that do not fit the LDS pool
-  static constexpr int SPILL = (NP > POOL ? NP - POOL : 0);
+  static constexpr int SPILL = (NP > NREG + POOL ? NP - NREG - POOL : 0);
   static constexpr int G_SPILL = align_up(L.state_words, 4);
   static constexpr int REC_WORDS = align_up(G_SPILL + SPILL * kRecW, 32);
   // LDS image of one environment: scene words, then derived data
@@ -124,8 +131,11 @@ struct Cfg {
   static constexpr int LCAP = 16;                          // a level holds at most one pair per movable shape
   static constexpr int X_SCHED = X_LIST + LIST_W;          // bytes [R][LCAP]: pool indices, level by level
   static constexpr int X_PSTATE = align_up(X_SCHED + R * LCAP / 4, 4);   // bytes [G][16]: active-point bits of pair (r, k) at [k][r]
-  static constexpr int X_BITMAP = X_PSTATE + GP * 4;       // 4 words: bit id set = pair id is active this substep
-  static constexpr int X_POOL = X_BITMAP + 4;
+  static constexpr int X_BITMAP = X_PSTATE + GP * 4;       // 4 words: bit id set = pair id is active this substep;
+                                                           // 4 more: ... and is not held in registers
+  static constexpr int X_DUMP = X_BITMAP + 8;              // 2N+1 words that swallow the velocity stores of shapes no
+                                                           // impulse moves (at offsets 0, N, 2N)
+  static constexpr int X_POOL = align_up(X_DUMP + 2 * N + 1, 2);
   static constexpr int LDS_WORDS = X_POOL + POOL * kRecW;
   // stride = odd multiple of G words: the same word of different environments falls into different banks
   static constexpr int LDS_STRIDE = align_up(LDS_WORDS - G, 2 * G) + G;
@@ -199,7 +209,7 @@ __device__ __forceinline__ void apply_impulse(float& vx, float& vy, float& w, fl
 // One active pair of the current substep.  Body indices and per-point activity are packed in `ab`.
 struct PairRec {
   float nx, ny, mu, corr;        // unit normal a->b; friction coefficient; positional-correction length
-  int ab;                        // a | b<<8 | active0<<16 | active1<<17
+  int ab;                        // a | b<<8 | active0<<16 | active1<<17 | pair id<<18
   float rax[2], ray[2], rbx[2], rby[2], mass_n[2], mass_t[2], bias[2], rest[2], lam_n[2], lam_t[2];
 };
 
@@ -405,13 +415,10 @@ struct Step {
   }
 
   // One visit of an active pair in a solver sweep: per point, normal impulse then friction impulse,
-  // accumulated and clamped (A.3.5, A.3.6, A.7).  Velocities are read from and written to LDS.
-  static __device__ __forceinline__ void solve_pair(float* E, PairRec& rc, unsigned fixed) {
-    const int a = rc.ab & 0xff, b = (rc.ab >> 8) & 0xff;
-    float vax = E[L.vel_x + a], vay = E[L.vel_y + a], wa = E[L.omega + a];
-    float vbx = E[L.vel_x + b], vby = E[L.vel_y + b], wb = E[L.omega + b];
-    const float ima = E[L.inv_mass + a], iia = E[L.inv_inertia + a];
-    const float imb = E[L.inv_mass + b], iib = E[L.inv_inertia + b];
+  // accumulated and clamped (A.3.5, A.3.6, A.7), on the velocities of its two bodies.
+  static __device__ __forceinline__ void solve_points(PairRec& rc, float ima, float iia, float imb, float iib,
+                                                      float& vax, float& vay, float& wa, float& vbx, float& vby,
+                                                      float& wb) {
     const float tx = -rc.ny, ty = rc.nx;
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
@@ -438,17 +445,11 @@ struct Step {
         apply_impulse(vbx, vby, wb, imb, iib, -fx, -fy, rc.rbx[k], rc.rby[k]);
       }
     }
-    if (!((fixed >> a) & 1u)) { E[L.vel_x + a] = vax; E[L.vel_y + a] = vay; E[L.omega + a] = wa; }
-    if (!((fixed >> b) & 1u)) { E[L.vel_x + b] = vbx; E[L.vel_y + b] = vby; E[L.omega + b] = wb; }
   }
-
   // Warm starting of one pair (A.7): re-apply the kept accumulated impulses.
-  static __device__ __forceinline__ void warm_pair(float* E, const PairRec& rc, unsigned fixed) {
-    const int a = rc.ab & 0xff, b = (rc.ab >> 8) & 0xff;
-    float vax = E[L.vel_x + a], vay = E[L.vel_y + a], wa = E[L.omega + a];
-    float vbx = E[L.vel_x + b], vby = E[L.vel_y + b], wb = E[L.omega + b];
-    const float ima = E[L.inv_mass + a], iia = E[L.inv_inertia + a];
-    const float imb = E[L.inv_mass + b], iib = E[L.inv_inertia + b];
+  static __device__ __forceinline__ void warm_points(const PairRec& rc, float ima, float iia, float imb, float iib,
+                                                     float& vax, float& vay, float& wa, float& vbx, float& vby,
+                                                     float& wb) {
     const float tx = -rc.ny, ty = rc.nx;
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
@@ -459,13 +460,56 @@ struct Step {
         apply_impulse(vbx, vby, wb, imb, iib, -jx, -jy, rc.rbx[k], rc.rby[k]);
       }
     }
+  }
+
+  // A pair whose record is not held in registers (LDS pool or HBM): velocities through LDS, the bodies'
+  // constants looked up per visit.  WARM selects warm starting instead of a solver visit.
+  template <bool WARM>
+  static __device__ __forceinline__ void visit_pair(float* E, PairRec& rc, unsigned fixed) {
+    const int a = rc.ab & 0xff, b = (rc.ab >> 8) & 0xff;
+    float vax = E[L.vel_x + a], vay = E[L.vel_y + a], wa = E[L.omega + a];
+    float vbx = E[L.vel_x + b], vby = E[L.vel_y + b], wb = E[L.omega + b];
+    const float ima = E[L.inv_mass + a], iia = E[L.inv_inertia + a];
+    const float imb = E[L.inv_mass + b], iib = E[L.inv_inertia + b];
+    if (WARM) warm_points(rc, ima, iia, imb, iib, vax, vay, wa, vbx, vby, wb);
+    else solve_points(rc, ima, iia, imb, iib, vax, vay, wa, vbx, vby, wb);
     if (!((fixed >> a) & 1u)) { E[L.vel_x + a] = vax; E[L.vel_y + a] = vay; E[L.omega + a] = wa; }
     if (!((fixed >> b) & 1u)) { E[L.vel_x + b] = vbx; E[L.vel_y + b] = vby; E[L.omega + b] = wb; }
+  }
+
+  // An active pair that a lane keeps in registers for one substep.
+  struct Own {
+    PairRec rc;
+    float ima, iia, imb, iib;
+    int pa, pb;   // shape indices
+    int sa, sb;   // where the velocities go back: the shape itself, or the dump slot if no impulse moves it
+    int id;       // pair id in canonical order, -1 = nothing held
+    int lv;       // dependency level of this substep
+  };
+  static __device__ __forceinline__ void load_own(float* E, int slot, unsigned fixed, Own& o) {
+    rec_load(to_lds(E + K::X_POOL + slot * kRecW), o.rc);
+    const int a = o.rc.ab & 0xff, b = (o.rc.ab >> 8) & 0xff;
+    o.ima = E[L.inv_mass + a]; o.iia = E[L.inv_inertia + a];
+    o.imb = E[L.inv_mass + b]; o.iib = E[L.inv_inertia + b];
+    o.pa = a; o.pb = b;
+    o.sa = ((fixed >> a) & 1u) ? K::X_DUMP - L.vel_x : a;
+    o.sb = ((fixed >> b) & 1u) ? K::X_DUMP - L.vel_x : b;
+    o.id = (o.rc.ab >> 18) & 127;
+    o.lv = -1;
+  }
+  template <bool WARM>
+  static __device__ __forceinline__ void visit_own(float* E, Own& o) {
+    float vax = E[L.vel_x + o.pa], vay = E[L.vel_y + o.pa], wa = E[L.omega + o.pa];
+    float vbx = E[L.vel_x + o.pb], vby = E[L.vel_y + o.pb], wb = E[L.omega + o.pb];
+    if (WARM) warm_points(o.rc, o.ima, o.iia, o.imb, o.iib, vax, vay, wa, vbx, vby, wb);
+    else solve_points(o.rc, o.ima, o.iia, o.imb, o.iib, vax, vay, wa, vbx, vby, wb);
+    E[L.vel_x + o.sa] = vax; E[L.vel_y + o.sa] = vay; E[L.omega + o.sa] = wa;
+    E[L.vel_x + o.sb] = vbx; E[L.vel_y + o.sb] = vby; E[L.omega + o.sb] = wb;
   }
 };
 
 template <class K>
-__global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state, const float* __restrict__ actions,
+__global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ state, const float* __restrict__ actions,
                                                       int n_envs, int n_steps, Params prm) {
   using S = Step<K>;
   constexpr k2d_layout L = K::L;
@@ -717,7 +761,11 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       // 2. the surviving pair ids of the environment are gathered into one list, one shape-type mix
       //    after the other, so that the group's lanes share them evenly and a wavefront runs one kind
       //    of manifold code per trip;
-      // 3. every active pair becomes a record in the pool.
+      // 3. every active pair becomes a record and is handed, through an LDS slot, to the lane that keeps
+      //    it in registers for the rest of the substep (pairs beyond two per lane stay in LDS / HBM).
+      typename S::Own oa, ob;
+      oa.id = -1; ob.id = -1; oa.lv = -1; ob.lv = -1;
+      oa.rc.ab = 0; ob.rc.ab = 0;
       unsigned cand = 0u;
 #pragma unroll
       for (int r = 0; r < R; ++r) {
@@ -739,7 +787,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         }
         for (unsigned st = nz & ~cand & my_r; st != 0u; st &= st - 1u) pstate[kp * 16 + (__ffs(st) - 1)] = 0;
       }
-      if (k < 4) bitmap[k] = 0u;
+      if (k < 8) bitmap[k] = 0u;
       int kind_n[3], kind_off[3];
       {
         const unsigned m0 = cand & pp_mask, m1 = cand & pc_mask, m2 = cand & ~(pp_mask | pc_mask);
@@ -784,12 +832,13 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
         const bool active = act0 || act1;
         unsigned long long bal = __ballot(active);
         unsigned envbits = (unsigned)(bal >> (g * G)) & (G >= 32 ? 0xffffffffu : ((1u << (G & 31)) - 1u));
-        int idx = pool_base + __popc(envbits & ((1u << k) - 1u));
-        pool_base += __popc(envbits);
+        const int trip_base = pool_base, trip_n = __popc(envbits);
+        int idx = trip_base + __popc(envbits & ((1u << k) - 1u));
+        pool_base += trip_n;
         if (active) {
           PairRec rc;
           rc.nx = m.nx; rc.ny = m.ny;
-          rc.ab = a | (b << 8) | ((int)act0 << 16) | ((int)act1 << 17);
+          rc.ab = a | (b << 8) | ((int)act0 << 16) | ((int)act1 << 17) | (id << 18);
           const float ima = E[L.inv_mass + a], iia = E[L.inv_inertia + a];
           const float imb = E[L.inv_mass + b], iib = E[L.inv_inertia + b];
           const float fa = E[L.friction + a], fb = E[L.friction + b];
@@ -828,12 +877,22 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
             if (on) pen = fmaxf(pen, m.pen[q]);
           }
           rc.corr = prm.beta * fmaxf(pen - prm.slop, 0.f) / (ima + imb);          // A.3.7
-          if (idx < K::POOL) rec_store(to_lds(pool + idx * kRecW), rc);
-          else rec_store(spill + (idx - K::POOL) * kRecW, rc);
+          if (idx < K::NREG + K::POOL) rec_store(to_lds(pool + (idx & (G - 1)) * kRecW), rc);
+          else rec_store(spill + (idx - K::NREG - K::POOL) * kRecW, rc);
           table[id] = (unsigned char)idx;
           atomicOr(&bitmap[id >> 5], 1u << (id & 31));
+          if (idx >= K::NREG) atomicOr(&bitmap[4 + (id >> 5)], 1u << (id & 31));
         }
         if (have) pstate[kk * 16 + r] = (unsigned char)((unsigned)act0 | ((unsigned)act1 << 1));
+        if (bal != 0ull) {   // hand-over: pair idx of this trip sits in slot idx % G, lane idx % G takes it
+          __syncthreads();
+          const int my = trip_base + ((k - trip_base) & (G - 1));
+          if (my < trip_base + trip_n) {
+            if (my < G) S::load_own(E, k, static_mask, oa);
+            else if (my < K::NREG) S::load_own(E, k, static_mask, ob);
+          }
+          __syncthreads();
+        }
        }
       }
       __syncthreads();
@@ -842,15 +901,18 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       // one level touch disjoint movable shapes and pairs that share one keep their canonical order, so
       // sweeping the levels in order, each level at once, gives the same bits as the sequential sweep --
       // in far fewer trips (everything resting on the static floor is one level; a level never exceeds
-      // the round).  Every lane walks the whole table in registers (no barrier); lane s mod G writes
-      // entry s of a level.
-      unsigned long long level_cnt = 0ull;   // pairs per level, 4 bits each (a level holds fewer than 16)
+      // the round).  Every lane walks the whole table in registers (no barrier) and notes the level of
+      // the pairs it holds; the pairs that are not held in registers are listed level by level (lane
+      // s mod G writes entry s of a level).
+      unsigned long long level_cnt = 0ull;   // listed pairs per level, 4 bits each (a level holds fewer than 16)
       int n_clevels = 0;
       {
         unsigned long long nxt = 0ull;       // next free level of every shape, 4 bits each
         const uint4 bm = *reinterpret_cast<const uint4*>(bitmap);
+        const uint4 bl = *reinterpret_cast<const uint4*>(bitmap + 4);
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
+          const unsigned listed = w == 0 ? bl.x : w == 1 ? bl.y : w == 2 ? bl.z : bl.w;
           for (unsigned bits = w == 0 ? bm.x : w == 1 ? bm.y : w == 2 ? bm.z : bm.w; bits != 0u; bits &= bits - 1u) {
             const int id = 32 * w + __ffs(bits) - 1;
             int a, b;
@@ -860,9 +922,13 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
             const int lv = max(la, lb);
             if (da) nxt = (nxt & ~(15ull << (4 * a))) | ((unsigned long long)(lv + 1) << (4 * a));
             if (db) nxt = (nxt & ~(15ull << (4 * b))) | ((unsigned long long)(lv + 1) << (4 * b));
-            const int slot = (int)((level_cnt >> (4 * lv)) & 15ull);
-            level_cnt += 1ull << (4 * lv);
-            if ((slot & (G - 1)) == k) sched[lv * K::LCAP + slot] = table[id];
+            if (id == oa.id) oa.lv = lv;
+            if (id == ob.id) ob.lv = lv;
+            if ((listed >> (id & 31)) & 1u) {
+              const int slot = (int)((level_cnt >> (4 * lv)) & 15ull);
+              level_cnt += 1ull << (4 * lv);
+              if ((slot & (G - 1)) == k) sched[lv * K::LCAP + slot] = table[id];
+            }
             n_clevels = max(n_clevels, lv + 1);
           }
         }
@@ -872,25 +938,32 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       for (int lv = 1; lv <= R; ++lv)
         if (__any(n_clevels >= lv)) wave_clevels = lv;
       __syncthreads();
-      // every lane may serve any pair: the lanes of the group take the entries of a level G at a time
-      auto for_each_level = [&](auto&& f) {
+      // one level at a time: the pairs held in registers (first and second of the lane), then the listed ones
+      const bool any_b = __any(ob.id >= 0), any_listed = __any(level_cnt != 0ull);
+      auto for_each_level = [&](auto&& f_own, auto&& f_listed) {
         for (int lv = 0; lv < wave_clevels; ++lv) {
-          const int c = cnt_of(lv);
-          for (int base = 0; __any(base < c); base += G) {
-            if (base + k < c) f((int)sched[lv * K::LCAP + base + k]);
-            __syncthreads();
+          if (oa.lv == lv) f_own(oa);
+          if (any_b) {
+            if (ob.lv == lv) f_own(ob);
           }
+          if (any_listed) {
+            const int c = cnt_of(lv);
+            for (int base = 0; __any(base < c); base += G)
+              if (base + k < c) f_listed((int)sched[lv * K::LCAP + base + k] - K::NREG);
+          }
+          __syncthreads();
         }
       };
 
       // ---- warm starting (Alg. 1, A.7): collisions in canonical order, then joints ----
       if (prm.warm_start) {
-        for_each_level([&](int idx) {
-          PairRec rc;
-          if (idx < K::POOL) rec_load(to_lds(pool + idx * kRecW), rc);
-          else rec_load(spill + (idx - K::POOL) * kRecW, rc);
-          S::warm_pair(E, rc, static_mask);
-        });
+        for_each_level([&](typename S::Own& o) { S::template visit_own<true>(E, o); },
+                       [&](int q) {
+                         PairRec rc;
+                         if (q < K::POOL) rec_load(to_lds(pool + q * kRecW), rc);
+                         else rec_load(spill + (q - K::POOL) * kRecW, rc);
+                         S::template visit_pair<true>(E, rc, static_mask);
+                       });
         for (int lv = 0; lv < wave_levels; ++lv) {
           if (k < J && j_live && j_level == lv) {
             float wa = E[L.omega + ja], wb = E[L.omega + jb];
@@ -937,24 +1010,25 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           }
           __syncthreads();
         }
-        for_each_level([&](int idx) {
-          // (the two branches keep LDS and HBM accesses apart: a merged pointer would turn every access
-          // into a slow flat one)
-          PairRec rc;
-          if (idx < K::POOL) {
-            LdsF rp = to_lds(pool + idx * kRecW);
-            rec_load(rp, rc);
-            S::solve_pair(E, rc, static_mask);
+        for_each_level([&](typename S::Own& o) { S::template visit_own<false>(E, o); },
+                       [&](int q) {
+                         // (the two branches keep LDS and HBM accesses apart: a merged pointer would turn
+                         // every access into a slow flat one)
+                         PairRec rc;
+                         if (q < K::POOL) {
+                           LdsF rp = to_lds(pool + q * kRecW);
+                           rec_load(rp, rc);
+                           S::template visit_pair<false>(E, rc, static_mask);
 #pragma unroll
-            for (int q = 0; q < 2; ++q) { rp[5 + 10 * q + 8] = rc.lam_n[q]; rp[5 + 10 * q + 9] = rc.lam_t[q]; }
-          } else {
-            float* rp = spill + (idx - K::POOL) * kRecW;
-            rec_load(rp, rc);
-            S::solve_pair(E, rc, static_mask);
+                           for (int z = 0; z < 2; ++z) { rp[5 + 10 * z + 8] = rc.lam_n[z]; rp[5 + 10 * z + 9] = rc.lam_t[z]; }
+                         } else {
+                           float* rp = spill + (q - K::POOL) * kRecW;
+                           rec_load(rp, rc);
+                           S::template visit_pair<false>(E, rc, static_mask);
 #pragma unroll
-            for (int q = 0; q < 2; ++q) { rp[5 + 10 * q + 8] = rc.lam_n[q]; rp[5 + 10 * q + 9] = rc.lam_t[q]; }
-          }
-        });
+                           for (int z = 0; z < 2; ++z) { rp[5 + 10 * z + 8] = rc.lam_n[z]; rp[5 + 10 * z + 9] = rc.lam_t[z]; }
+                         }
+                       });
       }
 
       // ---- Euler step of position and rotation (Alg. 1) ----
@@ -973,19 +1047,7 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
       __syncthreads();
 
       // ---- positional corrections (A.3.7, A.4.1); the pair's accumulated impulses go to HBM ----
-      for_each_level([&](int idx) {
-        float nx, ny, corr;
-        int ab;
-        float4 lam;
-        if (idx < K::POOL) {
-          LdsF rp = to_lds(pool + idx * kRecW);
-          nx = rp[0]; ny = rp[1]; corr = rp[3]; ab = f2i(rp[4]);
-          lam = make_float4(rp[13], rp[14], rp[23], rp[24]);
-        } else {
-          const float* rp = spill + (idx - K::POOL) * kRecW;
-          nx = rp[0]; ny = rp[1]; corr = rp[3]; ab = f2i(rp[4]);
-          lam = make_float4(rp[13], rp[14], rp[23], rp[24]);
-        }
+      auto correct = [&](float nx, float ny, float corr, int ab, float4 lam) {
         const int a = ab & 0xff, b = (ab >> 8) & 0xff;
         // the pair's accumulated impulses wait in the HBM record for the next substep (A.7)
         if (env_ok) *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(a, b)) = lam;
@@ -998,7 +1060,20 @@ __global__ void __launch_bounds__(64) k2d_step_kernel(float* __restrict__ state,
           E[L.pos_x + b] = E[L.pos_x + b] + (imb * corr) * nx;
           E[L.pos_y + b] = E[L.pos_y + b] + (imb * corr) * ny;
         }
-      });
+      };
+      for_each_level([&](typename S::Own& o) {
+                       correct(o.rc.nx, o.rc.ny, o.rc.corr, o.rc.ab,
+                               make_float4(o.rc.lam_n[0], o.rc.lam_t[0], o.rc.lam_n[1], o.rc.lam_t[1]));
+                     },
+                     [&](int q) {
+                       if (q < K::POOL) {
+                         LdsCF rp = to_lds(pool + q * kRecW);
+                         correct(rp[0], rp[1], rp[3], f2i(rp[4]), make_float4(rp[13], rp[14], rp[23], rp[24]));
+                       } else {
+                         const float* rp = spill + (q - K::POOL) * kRecW;
+                         correct(rp[0], rp[1], rp[3], f2i(rp[4]), make_float4(rp[13], rp[14], rp[23], rp[24]));
+                       }
+                     });
       for (int lv = 0; lv < wave_levels; ++lv) {
         if (k < J && j_live && j_level == lv) {
           float ca = E[K::X_COS + ja], sa = E[K::X_SIN + ja], cb = E[K::X_COS + jb], sb = E[K::X_SIN + jb];
@@ -1169,9 +1244,9 @@ __global__ void k2d_contacts_kernel(const float* state, uint8_t* pair_count, uin
 #ifndef K2D_H_L
 #define K2D_H_L 2
 #endif
-using CfgS = Cfg<5, 2, 1, 1, 21, 4>;
-using CfgM = Cfg<6, 3, 2, 2, 36, 2>;
-using CfgL = Cfg<12, 4, 6, 2, 17, K2D_H_L>;
+using CfgS = Cfg<5, 2, 1, 1, 4>;
+using CfgM = Cfg<6, 3, 2, 2, 2>;
+using CfgL = Cfg<12, 4, 6, 2, K2D_H_L>;
 // four L wavefronts must share one CU's 160 KiB of LDS: with 8192 environments every SIMD then holds one
 static_assert(CfgL::LDS_BYTES * CfgL::G <= 40960 * 8, "L image too large: every SIMD must be able to hold 16 L environments' worth of lanes");
 
