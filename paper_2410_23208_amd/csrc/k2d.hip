@@ -107,10 +107,10 @@ struct Cfg {
   static_assert(PPR <= 8 && J <= G && T <= G && R <= 15 && G == 16 && (H & (H - 1)) == 0,
                 "capacity class does not fit the lane mapping");
   // Active pairs are numbered 0, 1, ... as the narrowphase finds them.  Pairs below NREG live in
-  // registers (lane k holds pairs k and G + k), the next POOL in LDS, the rest in the HBM record.  The
-  // POOL slots also stage the hand-over of a register-held record from the lane that computed it to the
-  // lane that keeps it: pair idx always uses slot idx % G.
-  static constexpr int NREG = 2 * G, POOL = G;
+  // registers (lane k holds pairs k and G + k): the lane that found the manifold leaves it in an LDS
+  // staging slot, the lane that keeps the pair derives the substep constants from it.  The next POOL
+  // pairs live as full records in LDS, the rest in the HBM record.
+  static constexpr int NREG = 2 * G, POOL = 4, kManW = 9;
   static constexpr k2d_layout L = make_layout(P, C, J, T);
   // HBM record: state words, then room for the pair records that do not fit the LDS pool
   static constexpr int SPILL = (NP > NREG + POOL ? NP - NREG - POOL : 0);
@@ -135,7 +135,8 @@ struct Cfg {
                                                            // 4 more: ... and is not held in registers
   static constexpr int X_DUMP = X_BITMAP + 8;              // 2N+1 words that swallow the velocity stores of shapes no
                                                            // impulse moves (at offsets 0, N, 2N)
-  static constexpr int X_POOL = align_up(X_DUMP + 2 * N + 1, 2);
+  static constexpr int X_STAGE = X_DUMP + 2 * N + 1;       // staged manifolds, kManW words each
+  static constexpr int X_POOL = X_STAGE + NREG * kManW;
   static constexpr int LDS_WORDS = X_POOL + POOL * kRecW;
   // stride = odd multiple of G words: the same word of different environments falls into different banks
   static constexpr int LDS_STRIDE = align_up(LDS_WORDS - G, 2 * G) + G;
@@ -486,15 +487,70 @@ struct Step {
     int id;       // pair id in canonical order, -1 = nothing held
     int lv;       // dependency level of this substep
   };
-  static __device__ __forceinline__ void load_own(float* E, int slot, unsigned fixed, Own& o) {
-    rec_load(to_lds(E + K::X_POOL + slot * kRecW), o.rc);
-    const int a = o.rc.ab & 0xff, b = (o.rc.ab >> 8) & 0xff;
-    o.ima = E[L.inv_mass + a]; o.iia = E[L.inv_inertia + a];
-    o.imb = E[L.inv_mass + b]; o.iib = E[L.inv_inertia + b];
+  // Substep constants of an active pair from its manifold (A.3.5-A.3.7) and the accumulated impulses it
+  // keeps (A.7).  `w` packs a | b<<8 | active0<<16 | active1<<17 | pair id<<18 | active bits of the
+  // previous substep<<25; `lam` holds the stored impulses (n0, t0, n1, t1).
+  static __device__ __forceinline__ void presolve(const float* E, const Params& prm, const Manifold& m, int w,
+                                                  float4 lam, PairRec& rc, float& ima, float& iia, float& imb,
+                                                  float& iib) {
+    const int a = w & 0xff, b = (w >> 8) & 0xff;
+    const bool act0 = (w >> 16) & 1, act1 = (w >> 17) & 1;
+    const unsigned prev = (unsigned)(w >> 25) & 3u;
+    rc.nx = m.nx; rc.ny = m.ny;
+    rc.ab = w & 0x1ffffff;
+    ima = E[L.inv_mass + a]; iia = E[L.inv_inertia + a];
+    imb = E[L.inv_mass + b]; iib = E[L.inv_inertia + b];
+    const float fa = E[L.friction + a], fb = E[L.friction + b];
+    const float e = fminf(E[L.restitution + a], E[L.restitution + b]);   // A.3.5
+    rc.mu = sqrtf(fa * fa + fb * fb);                                        // A.3.6
+    const float pax = E[L.pos_x + a], pay = E[L.pos_y + a], pbx = E[L.pos_x + b], pby = E[L.pos_y + b];
+    const float vax = E[L.vel_x + a], vay = E[L.vel_y + a], wa = E[L.omega + a];
+    const float vbx = E[L.vel_x + b], vby = E[L.vel_y + b], wb = E[L.omega + b];
+    const float tx = -m.ny, ty = m.nx;
+    float pen = 0.f;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const bool on = q ? act1 : act0;
+      rc.rax[q] = m.px[q] - pax; rc.ray[q] = m.py[q] - pay;
+      rc.rbx[q] = m.px[q] - pbx; rc.rby[q] = m.py[q] - pby;
+      float ran = cross2(rc.rax[q], rc.ray[q], m.nx, m.ny), rbn = cross2(rc.rbx[q], rc.rby[q], m.nx, m.ny);
+      float rat = cross2(rc.rax[q], rc.ray[q], tx, ty), rbt = cross2(rc.rbx[q], rc.rby[q], tx, ty);
+      float kn = ima + imb + ran * ran * iia + rbn * rbn * iib;
+      float kt = ima + imb + rat * rat * iia + rbt * rbt * iib;
+      rc.mass_n[q] = on ? 1.f / kn : 0.f;
+      rc.mass_t[q] = on ? 1.f / kt : 0.f;
+      rc.bias[q] = prm.alpha * fmaxf(m.pen[q] - prm.slop, 0.f);            // A.3.7
+      // restitution target -e*v_r (A.3.5), v_r sampled here: after motors and thrusters,
+      // before any constraint impulse; slow approaches take e = 0
+      float rx, ry;
+      rel_vel(vax, vay, wa, rc.rax[q], rc.ray[q], vbx, vby, wb, rc.rbx[q], rc.rby[q], rx, ry);
+      float vn0 = dot2(m.nx, m.ny, rx, ry);
+      rc.rest[q] = (vn0 > prm.rest_thr) ? e * vn0 : 0.f;
+      bool keep = prm.warm_start && on && ((prev >> q) & 1u);                 // A.7
+      rc.lam_n[q] = keep ? (q ? lam.z : lam.x) : 0.f;
+      rc.lam_t[q] = keep ? (q ? lam.w : lam.y) : 0.f;
+      if (on) pen = fmaxf(pen, m.pen[q]);
+    }
+    rc.corr = prm.beta * fmaxf(pen - prm.slop, 0.f) / (ima + imb);          // A.3.7
+  }
+  // The lane that keeps pair idx picks its staged manifold up and derives the record in its own registers.
+  static __device__ __forceinline__ void take_own(const float* E, const float* Rg, const Params& prm, int idx,
+                                                  unsigned fixed, Own& o) {
+    LdsCF p = (LdsCF)(E + K::X_STAGE + idx * K::kManW);
+    Manifold m;
+    m.nx = p[0]; m.ny = p[1];
+    m.px[0] = p[2]; m.py[0] = p[3]; m.pen[0] = p[4];
+    m.px[1] = p[5]; m.py[1] = p[6]; m.pen[1] = p[7];
+    const int w = f2i(p[8]);
+    const int a = w & 0xff, b = (w >> 8) & 0xff;
+    float4 lam = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (prm.warm_start && ((w >> 25) & 3))
+      lam = *reinterpret_cast<const float4*>(Rg + L.lambda + 4 * pair_index(a, b));
+    presolve(E, prm, m, w, lam, o.rc, o.ima, o.iia, o.imb, o.iib);
     o.pa = a; o.pb = b;
     o.sa = ((fixed >> a) & 1u) ? K::X_DUMP - L.vel_x : a;
     o.sb = ((fixed >> b) & 1u) ? K::X_DUMP - L.vel_x : b;
-    o.id = (o.rc.ab >> 18) & 127;
+    o.id = (w >> 18) & 127;
     o.lv = -1;
   }
   template <bool WARM>
@@ -761,11 +817,8 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       // 2. the surviving pair ids of the environment are gathered into one list, one shape-type mix
       //    after the other, so that the group's lanes share them evenly and a wavefront runs one kind
       //    of manifold code per trip;
-      // 3. every active pair becomes a record and is handed, through an LDS slot, to the lane that keeps
-      //    it in registers for the rest of the substep (pairs beyond two per lane stay in LDS / HBM).
-      typename S::Own oa, ob;
-      oa.id = -1; ob.id = -1; oa.lv = -1; ob.lv = -1;
-      oa.rc.ab = 0; ob.rc.ab = 0;
+      // 3. the manifold of every active pair is staged in LDS for the lane that keeps the pair in
+      //    registers for the rest of the substep (pairs beyond two per lane become records in LDS / HBM).
       unsigned cand = 0u;
 #pragma unroll
       for (int r = 0; r < R; ++r) {
@@ -832,68 +885,42 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         const bool active = act0 || act1;
         unsigned long long bal = __ballot(active);
         unsigned envbits = (unsigned)(bal >> (g * G)) & (G >= 32 ? 0xffffffffu : ((1u << (G & 31)) - 1u));
-        const int trip_base = pool_base, trip_n = __popc(envbits);
-        int idx = trip_base + __popc(envbits & ((1u << k) - 1u));
-        pool_base += trip_n;
+        const int idx = pool_base + __popc(envbits & ((1u << k) - 1u));
+        pool_base += __popc(envbits);
         if (active) {
-          PairRec rc;
-          rc.nx = m.nx; rc.ny = m.ny;
-          rc.ab = a | (b << 8) | ((int)act0 << 16) | ((int)act1 << 17) | (id << 18);
-          const float ima = E[L.inv_mass + a], iia = E[L.inv_inertia + a];
-          const float imb = E[L.inv_mass + b], iib = E[L.inv_inertia + b];
-          const float fa = E[L.friction + a], fb = E[L.friction + b];
-          const float e = fminf(E[L.restitution + a], E[L.restitution + b]);   // A.3.5
-          rc.mu = sqrtf(fa * fa + fb * fb);                                        // A.3.6
-          const float pax = E[L.pos_x + a], pay = E[L.pos_y + a], pbx = E[L.pos_x + b], pby = E[L.pos_y + b];
-          const float vax = E[L.vel_x + a], vay = E[L.vel_y + a], wa = E[L.omega + a];
-          const float vbx = E[L.vel_x + b], vby = E[L.vel_y + b], wb = E[L.omega + b];
-          const float tx = -m.ny, ty = m.nx;
-          float4 lam = make_float4(0.f, 0.f, 0.f, 0.f);
-          const unsigned pb = pstate[kk * 16 + r];
-          if (prm.warm_start && pb != 0u)
-            lam = *reinterpret_cast<const float4*>(Rg + L.lambda + 4 * S::pair_index(a, b));
-          float pen = 0.f;
-#pragma unroll
-          for (int q = 0; q < 2; ++q) {
-            const bool on = q ? act1 : act0;
-            rc.rax[q] = m.px[q] - pax; rc.ray[q] = m.py[q] - pay;
-            rc.rbx[q] = m.px[q] - pbx; rc.rby[q] = m.py[q] - pby;
-            float ran = cross2(rc.rax[q], rc.ray[q], m.nx, m.ny), rbn = cross2(rc.rbx[q], rc.rby[q], m.nx, m.ny);
-            float rat = cross2(rc.rax[q], rc.ray[q], tx, ty), rbt = cross2(rc.rbx[q], rc.rby[q], tx, ty);
-            float kn = ima + imb + ran * ran * iia + rbn * rbn * iib;
-            float kt = ima + imb + rat * rat * iia + rbt * rbt * iib;
-            rc.mass_n[q] = on ? 1.f / kn : 0.f;
-            rc.mass_t[q] = on ? 1.f / kt : 0.f;
-            rc.bias[q] = prm.alpha * fmaxf(m.pen[q] - prm.slop, 0.f);            // A.3.7
-            // restitution target -e*v_r (A.3.5), v_r sampled here: after motors and thrusters,
-            // before any constraint impulse; slow approaches take e = 0
-            float rx, ry;
-            S::rel_vel(vax, vay, wa, rc.rax[q], rc.ray[q], vbx, vby, wb, rc.rbx[q], rc.rby[q], rx, ry);
-            float vn0 = dot2(m.nx, m.ny, rx, ry);
-            rc.rest[q] = (vn0 > prm.rest_thr) ? e * vn0 : 0.f;
-            bool keep = prm.warm_start && on && ((pb >> q) & 1u);                 // A.7
-            rc.lam_n[q] = keep ? (q ? lam.z : lam.x) : 0.f;
-            rc.lam_t[q] = keep ? (q ? lam.w : lam.y) : 0.f;
-            if (on) pen = fmaxf(pen, m.pen[q]);
+          const int w = a | (b << 8) | ((int)act0 << 16) | ((int)act1 << 17) | (id << 18) |
+                        ((int)pstate[kk * 16 + r] << 25);
+          if (idx < K::NREG) {   // staged for the lane that keeps it
+            LdsF p = to_lds(E + K::X_STAGE + idx * K::kManW);
+            p[0] = m.nx; p[1] = m.ny;
+            p[2] = m.px[0]; p[3] = m.py[0]; p[4] = m.pen[0];
+            p[5] = m.px[1]; p[6] = m.py[1]; p[7] = m.pen[1];
+            p[8] = i2f(w);
+          } else {               // beyond the register-held pairs: a full record in the LDS pool or in HBM
+            float4 lam = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (prm.warm_start && ((w >> 25) & 3))
+              lam = *reinterpret_cast<const float4*>(Rg + L.lambda + 4 * S::pair_index(a, b));
+            PairRec rc;
+            float ima, iia, imb, iib;
+            S::presolve(E, prm, m, w, lam, rc, ima, iia, imb, iib);
+            if (idx < K::NREG + K::POOL) rec_store(to_lds(pool + (idx - K::NREG) * kRecW), rc);
+            else rec_store(spill + (idx - K::NREG - K::POOL) * kRecW, rc);
+            atomicOr(&bitmap[4 + (id >> 5)], 1u << (id & 31));
           }
-          rc.corr = prm.beta * fmaxf(pen - prm.slop, 0.f) / (ima + imb);          // A.3.7
-          if (idx < K::NREG + K::POOL) rec_store(to_lds(pool + (idx & (G - 1)) * kRecW), rc);
-          else rec_store(spill + (idx - K::NREG - K::POOL) * kRecW, rc);
           table[id] = (unsigned char)idx;
           atomicOr(&bitmap[id >> 5], 1u << (id & 31));
-          if (idx >= K::NREG) atomicOr(&bitmap[4 + (id >> 5)], 1u << (id & 31));
         }
         if (have) pstate[kk * 16 + r] = (unsigned char)((unsigned)act0 | ((unsigned)act1 << 1));
-        if (bal != 0ull) {   // hand-over: pair idx of this trip sits in slot idx % G, lane idx % G takes it
-          __syncthreads();
-          const int my = trip_base + ((k - trip_base) & (G - 1));
-          if (my < trip_base + trip_n) {
-            if (my < G) S::load_own(E, k, static_mask, oa);
-            else if (my < K::NREG) S::load_own(E, k, static_mask, ob);
-          }
-          __syncthreads();
-        }
        }
+      }
+      __syncthreads();
+      // lane k keeps active pairs k and G + k of its environment in registers
+      typename S::Own oa, ob;
+      oa.id = -1; ob.id = -1; oa.lv = -1; ob.lv = -1;
+      oa.rc.ab = 0; ob.rc.ab = 0;
+      if (k < pool_base) S::take_own(E, Rg, prm, k, static_mask, oa);
+      if (__any(pool_base > G)) {
+        if (k + G < pool_base && k + G < K::NREG) S::take_own(E, Rg, prm, k + G, static_mask, ob);
       }
       __syncthreads();
       // Dependency levels of the active pairs.  Walking the pairs in canonical order (= ascending id), a
