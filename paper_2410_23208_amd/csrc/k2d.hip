@@ -154,6 +154,14 @@ struct Params {   // device copy of k2d_params with the substep precomputed
 
 __device__ __forceinline__ int f2i(float f) { return __float_as_int(f); }
 
+// A workgroup of the step kernel is one wavefront, and the memory operations of one wavefront are
+// performed in the order they are issued: lanes that exchange data through LDS need no hardware barrier
+// and no wait, only a point that the compiler does not move memory accesses across.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
 // sin, cos and tanh as fixed sequences of IEEE fp32 operations (no maths-library call, no fused
 // multiply-add): quadrant reduction against a three-term split of pi/2, then polynomials in r*r; tanh
 // by polynomial below 0.55 and through e^{2|x|} above.  Any implementation that performs the same
@@ -591,7 +599,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       for (int w = lane; w < L.scene_words; w += 64) dst[w] = 0.f;   // all-inactive padding environment
     }
   }
-  __syncthreads();
+  wave_sync();
 
   // ---- per-launch derived data ----
   for (int i = k; i < N; i += G) {
@@ -613,7 +621,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     E[K::X_BRAD + i] = br;
     E[K::X_JOINED + i] = i2f(0);
   }
-  __syncthreads();
+  wave_sync();
   // joints: lane j of the group owns joint j for the whole launch
   bool j_live = false, j_fixed = false, j_motor = false;
   int ja = 0, jb = 0;
@@ -641,7 +649,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     }
     E[L.joint_flags + k] = i2f((fl & 7) | (j_live ? 8 : 0));
   }
-  __syncthreads();
+  wave_sync();
   // Shapes that no impulse can move (no inverse mass, no inverse inertia; inactive ones too).  An
   // impulse leaves their velocity and position exactly as they are, so constraints that share only
   // such a shape do not depend on each other, and nothing is ever written back for them.
@@ -696,7 +704,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
   unsigned elig = 0u, pp_mask = 0u, pc_mask = 0u;
   if (k < GP)
     for (int r = 0; r < 16; ++r) pstate[k * 16 + r] = 0;
-  __syncthreads();
+  wave_sync();
   unsigned my_r = 0u;   // the rounds this lane takes
   for (int r = 0; r < R; ++r)
     if (r % H == rpar) my_r |= 1u << r;
@@ -716,7 +724,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       }
     }
   }
-  __syncthreads();   // the joined-shape words share their LDS with the candidate list
+  wave_sync();   // the joined-shape words share their LDS with the candidate list
   float* pool = E + K::X_POOL;
   float* spill = Rg + K::G_SPILL;
   const float h = prm.h;
@@ -756,7 +764,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
           }
         }
       }
-      __syncthreads();
+      wave_sync();
 
       // ---- joint constants of this substep; motor and thruster impulses from the same velocities ----
       float j_rax = 0.f, j_ray = 0.f, j_rbx = 0.f, j_rby = 0.f, j_k11 = 0.f, j_k12 = 0.f, j_k22 = 0.f;
@@ -793,13 +801,13 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         float f = t_power * act_t * h;
         t_ix = f * dx; t_iy = f * dy;
       }
-      __syncthreads();
+      wave_sync();
       for (int lv = 0; lv < wave_levels; ++lv) {
         if (k < J && j_live && j_level == lv && motor != 0.f) {
           if (!ja_fix) E[L.omega + ja] = E[L.omega + ja] - j_iia * motor;
           if (!jb_fix) E[L.omega + jb] = E[L.omega + jb] + j_iib * motor;
         }
-        __syncthreads();
+        wave_sync();
       }
       for (int t = 0; t < T; ++t) {
         if (k == t && t_live) {
@@ -808,7 +816,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
           E[L.vel_y + t_body] = fmaf(im, t_iy, E[L.vel_y + t_body]);
           E[L.omega + t_body] = fmaf(ii, cross2(t_rx, t_ry, t_ix, t_iy), E[L.omega + t_body]);
         }
-        __syncthreads();
+        wave_sync();
       }
 
       // ---- collision manifolds of all eligible pairs (A.3.1-A.3.4) and their substep constants ----
@@ -859,7 +867,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         for (unsigned mm = m1; mm != 0u; mm &= mm - 1u) cand_list[w1++] = (unsigned char)((__ffs(mm) - 1) * GP + kp);
         for (unsigned mm = m2; mm != 0u; mm &= mm - 1u) cand_list[w2++] = (unsigned char)((__ffs(mm) - 1) * GP + kp);
       }
-      __syncthreads();
+      wave_sync();
       int pool_base = 0;
       for (int kind = 0; kind < 3; ++kind) {
        const int n_kind = kind_n[kind], off_kind = kind_off[kind];
@@ -913,7 +921,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         if (have) pstate[kk * 16 + r] = (unsigned char)((unsigned)act0 | ((unsigned)act1 << 1));
        }
       }
-      __syncthreads();
+      wave_sync();
       // lane k keeps active pairs k and G + k of its environment in registers
       typename S::Own oa, ob;
       oa.id = -1; ob.id = -1; oa.lv = -1; ob.lv = -1;
@@ -922,7 +930,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       if (__any(pool_base > G)) {
         if (k + G < pool_base && k + G < K::NREG) S::take_own(E, Rg, prm, k + G, static_mask, ob);
       }
-      __syncthreads();
+      wave_sync();
       // Dependency levels of the active pairs.  Walking the pairs in canonical order (= ascending id), a
       // pair goes one level after the last earlier pair that shares a movable shape with it.  Pairs of
       // one level touch disjoint movable shapes and pairs that share one keep their canonical order, so
@@ -964,7 +972,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       int wave_clevels = 0;
       for (int lv = 1; lv <= R; ++lv)
         if (__any(n_clevels >= lv)) wave_clevels = lv;
-      __syncthreads();
+      wave_sync();
       // one level at a time: the pairs held in registers (first and second of the lane), then the listed ones
       const bool any_b = __any(ob.id >= 0), any_listed = __any(level_cnt != 0ull);
       auto for_each_level = [&](auto&& f_own, auto&& f_listed) {
@@ -978,7 +986,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
             for (int base = 0; __any(base < c); base += G)
               if (base + k < c) f_listed((int)sched[lv * K::LCAP + base + k] - K::NREG);
           }
-          __syncthreads();
+          wave_sync();
         }
       };
 
@@ -1009,7 +1017,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
               E[L.omega + jb] = fmaf(j_iib, cross2(j_rbx, j_rby, -j_accx, -j_accy), wb);
             }
           }
-          __syncthreads();
+          wave_sync();
         }
       }
 
@@ -1035,7 +1043,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
             if (!ja_fix) { E[L.vel_x + ja] = vax; E[L.vel_y + ja] = vay; E[L.omega + ja] = wa; }
             if (!jb_fix) { E[L.vel_x + jb] = vbx; E[L.vel_y + jb] = vby; E[L.omega + jb] = wb; }
           }
-          __syncthreads();
+          wave_sync();
         }
         for_each_level([&](typename S::Own& o) { S::template visit_own<false>(E, o); },
                        [&](int q) {
@@ -1071,7 +1079,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
           E[K::X_SIN + i] = sn;
         }
       }
-      __syncthreads();
+      wave_sync();
 
       // ---- positional corrections (A.3.7, A.4.1); the pair's accumulated impulses go to HBM ----
       auto correct = [&](float nx, float ny, float corr, int ab, float4 lam) {
@@ -1117,7 +1125,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
             E[L.pos_y + jb] = E[L.pos_y + jb] + j_imb * cy;
           }
         }
-        __syncthreads();
+        wave_sync();
       }
     }
   }
@@ -1128,7 +1136,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     E[L.acc_y + k] = j_accy;
     E[L.acc_ang + k] = j_acca;
   }
-  __syncthreads();
+  wave_sync();
   for (int e = 0; e < K::EPW; ++e) {
     if (env0 + e < n_envs) {
       const float* src = lds + e * K::LDS_STRIDE;
