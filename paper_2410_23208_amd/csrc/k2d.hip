@@ -104,7 +104,7 @@ struct Cfg {
   static constexpr int G = GP * H;             // lanes per environment: lane k tests pair k % GP of the rounds
                                                // r with r % H == k / GP
   static constexpr int EPW = 64 / G;           // environments per wavefront
-  static_assert(PPR <= 8 && J <= G && T <= G && R <= 15 && G == 16 && (H & (H - 1)) == 0,
+  static_assert(PPR <= 8 && J <= G && T <= G && R <= 15 && G == 16 && (H & (H - 1)) == 0 && (R + H - 1) / H <= 8,
                 "capacity class does not fit the lane mapping");
   // Active pairs are numbered 0, 1, ... as the narrowphase finds them.  Pairs below NREG live in
   // registers (lane k holds pairs k and G + k): the lane that found the manifold leaves it in an LDS
@@ -708,9 +708,11 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
   unsigned my_r = 0u;   // the rounds this lane takes
   for (int r = 0; r < R; ++r)
     if (r % H == rpar) my_r |= 1u << r;
+  unsigned long long my_ab = 0ull;   // this lane's pairs, a | b << 4, eight bits for each of its rounds
   for (int r = 0; r < R; ++r) {
     int a, b;
     if (((my_r >> r) & 1u) && S::sched_pair(r, kp, a, b)) {
+      my_ab |= (unsigned long long)(a | (b << 4)) << (8 * (r / H));
       if (b < P) pp_mask |= 1u << r;
       else if (a < P) pc_mask |= 1u << r;
       bool ok = (f2i(E[L.shape_flags + a]) & 1) && (f2i(E[L.shape_flags + b]) & 1) &&
@@ -828,15 +830,17 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       // 3. the manifold of every active pair is staged in LDS for the lane that keeps the pair in
       //    registers for the rest of the substep (pairs beyond two per lane become records in LDS / HBM).
       unsigned cand = 0u;
+      {
+        const unsigned ab_lo = (unsigned)my_ab, ab_hi = (unsigned)(my_ab >> 32);
 #pragma unroll
-      for (int r = 0; r < R; ++r) {
-        if ((elig >> r) & 1u) {
-          int a, b;
-          S::sched_pair(r, kp, a, b);
+        for (int j = 0; j < (R + H - 1) / H; ++j) {   // round j * H + rpar: every lane is busy in every trip
+          const unsigned pk = ((j < 4 ? ab_lo : ab_hi) >> (8 * (j & 3))) & 0xffu;
+          const int a = pk & 15, b = pk >> 4;
           float dx = E[L.pos_x + b] - E[L.pos_x + a], dy = E[L.pos_y + b] - E[L.pos_y + a];
           float rr = (E[K::X_BRAD + a] + E[K::X_BRAD + b]) * 1.0001f + 1e-5f;
-          if (dx * dx + dy * dy <= rr * rr) cand |= 1u << r;
+          if (dx * dx + dy * dy <= rr * rr) cand |= 1u << (j * H + rpar);
         }
+        cand &= elig;
       }
       {   // pairs that were colliding and are not even candidates now: their points are no longer active
         uint4 ps = *reinterpret_cast<const uint4*>(pstate + kp * 16);
