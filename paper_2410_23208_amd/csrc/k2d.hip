@@ -131,12 +131,14 @@ struct Cfg {
   static constexpr int LCAP = 16;                          // a level holds at most one pair per movable shape
   static constexpr int X_SCHED = X_LIST + LIST_W;          // bytes [R][LCAP]: pool indices, level by level
   static constexpr int X_PSTATE = align_up(X_SCHED + R * LCAP / 4, 4);   // bytes [G][16]: active-point bits of pair (r, k) at [k][r]
-  static constexpr int X_BITMAP = X_PSTATE + GP * 4;       // 4 words: bit id set = pair id is active this substep;
-                                                           // 4 more: ... and is not held in registers
-  static constexpr int X_DUMP = X_BITMAP + 8;              // 2N+1 words that swallow the velocity stores of shapes no
-                                                           // impulse moves (at offsets 0, N, 2N)
-  static constexpr int X_STAGE = X_DUMP + 2 * N + 1;       // staged manifolds, kManW words each
+  static constexpr int X_BITMAP = X_PSTATE + GP * 4;       // 4 words: bit id set = pair id is active and not held in registers
+  static constexpr int X_RMASK = X_BITMAP + 4;             // [G] words: bit r set = the shape has an active pair in round r
+  static constexpr int X_LVL = X_RMASK + G;                // bytes [NID]: dependency level of pair id
+  static constexpr int X_STAGE = X_LVL + (NID + 3) / 4;    // staged manifolds, kManW words each
+  static constexpr int X_DUMP = X_STAGE;                   // (once the staged manifolds are taken) 2N+1 words that swallow the
+                                                           // velocity stores of shapes no impulse moves (offsets 0, N, 2N)
   static constexpr int X_POOL = X_STAGE + NREG * kManW;
+  static_assert(NREG * kManW >= 2 * N + 1, "dump slots do not fit the staging area");
   static constexpr int LDS_WORDS = X_POOL + POOL * kRecW;
   // stride = odd multiple of G words: the same word of different environments falls into different banks
   static constexpr int LDS_STRIDE = align_up(LDS_WORDS - G, 2 * G) + G;
@@ -727,6 +729,26 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     }
   }
   wave_sync();   // the joined-shape words share their LDS with the candidate list
+  // Lane s of the group also stands for shape s when dependency levels are worked out: for every round,
+  // its partner, the pair's slot in the round and whether the pair exists, eight bits per round.
+  unsigned rp[4] = {0u, 0u, 0u, 0u};
+  for (int r = 0; r < R; ++r) {
+    constexpr int M1 = K::M - 1;
+    int partner, ks;
+    if (k == M1) { partner = r; ks = 0; }
+    else if (k == r) { partner = M1; ks = 0; }
+    else {
+      int d = k - r; if (d < 0) d += M1;
+      if (d <= K::PPR - 1) { ks = d; partner = r - d; if (partner < 0) partner += M1; }
+      else { ks = M1 - d; partner = r + ks; if (partner >= M1) partner -= M1; }
+    }
+    const bool ok = k < N && partner < N;
+    const unsigned e = ok ? (unsigned)(partner | (ks << 4) | 0x80) : (unsigned)(k & (G - 1));   // no pair: look at oneself
+    rp[r >> 2] |= e << (8 * (r & 3));
+  }
+  const bool movable = k < N && !((static_mask >> k) & 1u);
+  unsigned* rmask = reinterpret_cast<unsigned*>(E + K::X_RMASK);
+  unsigned char* lvl = reinterpret_cast<unsigned char*>(E + K::X_LVL);
   float* pool = E + K::X_POOL;
   float* spill = Rg + K::G_SPILL;
   const float h = prm.h;
@@ -852,7 +874,8 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         }
         for (unsigned st = nz & ~cand & my_r; st != 0u; st &= st - 1u) pstate[kp * 16 + (__ffs(st) - 1)] = 0;
       }
-      if (k < 8) bitmap[k] = 0u;
+      if (k < 4) bitmap[k] = 0u;
+      rmask[k] = 0u;
       int kind_n[3], kind_off[3];
       {
         const unsigned m0 = cand & pp_mask, m1 = cand & pc_mask, m2 = cand & ~(pp_mask | pc_mask);
@@ -917,10 +940,11 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
             S::presolve(E, prm, m, w, lam, rc, ima, iia, imb, iib);
             if (idx < K::NREG + K::POOL) rec_store(to_lds(pool + (idx - K::NREG) * kRecW), rc);
             else rec_store(spill + (idx - K::NREG - K::POOL) * kRecW, rc);
-            atomicOr(&bitmap[4 + (id >> 5)], 1u << (id & 31));
+            atomicOr(&bitmap[id >> 5], 1u << (id & 31));
+            table[id] = (unsigned char)idx;
           }
-          table[id] = (unsigned char)idx;
-          atomicOr(&bitmap[id >> 5], 1u << (id & 31));
+          atomicOr(&rmask[a], 1u << r);
+          atomicOr(&rmask[b], 1u << r);
         }
         if (have) pstate[kk * 16 + r] = (unsigned char)((unsigned)act0 | ((unsigned)act1 << 1));
        }
@@ -935,50 +959,58 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         if (k + G < pool_base && k + G < K::NREG) S::take_own(E, Rg, prm, k + G, static_mask, ob);
       }
       wave_sync();
-      // Dependency levels of the active pairs.  Walking the pairs in canonical order (= ascending id), a
+      // Dependency levels of the active pairs.  Walking the pairs in canonical order (round by round), a
       // pair goes one level after the last earlier pair that shares a movable shape with it.  Pairs of
       // one level touch disjoint movable shapes and pairs that share one keep their canonical order, so
       // sweeping the levels in order, each level at once, gives the same bits as the sequential sweep --
       // in far fewer trips (everything resting on the static floor is one level; a level never exceeds
-      // the round).  Every lane walks the whole table in registers (no barrier) and notes the level of
-      // the pairs it holds; the pairs that are not held in registers are listed level by level (lane
-      // s mod G writes entry s of a level).
-      unsigned long long level_cnt = 0ull;   // listed pairs per level, 4 bits each (a level holds fewer than 16)
-      int n_clevels = 0;
+      // the round).  Lane s follows shape s: in every round the two lanes of an active pair exchange the
+      // next free level of their shapes and both move on to one past the larger.
+      int n_clevels = 0;   // next free level of this lane's shape
       {
-        unsigned long long nxt = 0ull;       // next free level of every shape, 4 bits each
-        const uint4 bm = *reinterpret_cast<const uint4*>(bitmap);
-        const uint4 bl = *reinterpret_cast<const uint4*>(bitmap + 4);
+        const unsigned rm = rmask[k];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          const unsigned listed = w == 0 ? bl.x : w == 1 ? bl.y : w == 2 ? bl.z : bl.w;
-          for (unsigned bits = w == 0 ? bm.x : w == 1 ? bm.y : w == 2 ? bm.z : bm.w; bits != 0u; bits &= bits - 1u) {
-            const int id = 32 * w + __ffs(bits) - 1;
-            int a, b;
-            S::sched_pair(id / GP, id % GP, a, b);
-            const bool da = !((static_mask >> a) & 1u), db = !((static_mask >> b) & 1u);
-            const int la = da ? (int)((nxt >> (4 * a)) & 15ull) : 0, lb = db ? (int)((nxt >> (4 * b)) & 15ull) : 0;
-            const int lv = max(la, lb);
-            if (da) nxt = (nxt & ~(15ull << (4 * a))) | ((unsigned long long)(lv + 1) << (4 * a));
-            if (db) nxt = (nxt & ~(15ull << (4 * b))) | ((unsigned long long)(lv + 1) << (4 * b));
-            if (id == oa.id) oa.lv = lv;
-            if (id == ob.id) ob.lv = lv;
-            if ((listed >> (id & 31)) & 1u) {
-              const int slot = (int)((level_cnt >> (4 * lv)) & 15ull);
-              level_cnt += 1ull << (4 * lv);
-              if ((slot & (G - 1)) == k) sched[lv * K::LCAP + slot] = table[id];
+        for (int r = 0; r < R; ++r) {
+          const unsigned e = (rp[r >> 2] >> (8 * (r & 3))) & 0xffu;
+          const bool act = (rm >> r) & 1u;
+          if (__any(act)) {
+            const int partner = e & 15;
+            const int mine = movable ? n_clevels : 0;
+            const int other = __shfl(mine, partner, G);
+            const int lv = max(mine, other);
+            if (act) {
+              if (movable) n_clevels = lv + 1;
+              if (k < partner) lvl[r * GP + ((e >> 4) & 7)] = (unsigned char)lv;
             }
-            n_clevels = max(n_clevels, lv + 1);
           }
         }
       }
-      auto cnt_of = [&](int lv) { return (int)((level_cnt >> (4 * lv)) & 15ull); };
       int wave_clevels = 0;
       for (int lv = 1; lv <= R; ++lv)
         if (__any(n_clevels >= lv)) wave_clevels = lv;
       wave_sync();
+      if (oa.id >= 0) oa.lv = lvl[oa.id];
+      if (ob.id >= 0) ob.lv = lvl[ob.id];
+      // the pairs that are not held in registers are listed level by level (lane s mod G writes entry s)
+      unsigned long long level_cnt = 0ull;   // listed pairs per level, 4 bits each (a level holds fewer than 16)
+      const uint4 bl = *reinterpret_cast<const uint4*>(bitmap);
+      const bool any_listed = __any((bl.x | bl.y | bl.z | bl.w) != 0u);
+      if (any_listed) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          for (unsigned bits = w == 0 ? bl.x : w == 1 ? bl.y : w == 2 ? bl.z : bl.w; bits != 0u; bits &= bits - 1u) {
+            const int id = 32 * w + __ffs(bits) - 1;
+            const int lv = lvl[id];
+            const int slot = (int)((level_cnt >> (4 * lv)) & 15ull);
+            level_cnt += 1ull << (4 * lv);
+            if ((slot & (G - 1)) == k) sched[lv * K::LCAP + slot] = table[id];
+          }
+        }
+        wave_sync();
+      }
+      auto cnt_of = [&](int lv) { return (int)((level_cnt >> (4 * lv)) & 15ull); };
       // one level at a time: the pairs held in registers (first and second of the lane), then the listed ones
-      const bool any_b = __any(ob.id >= 0), any_listed = __any(level_cnt != 0ull);
+      const bool any_b = __any(ob.id >= 0);
       auto for_each_level = [&](auto&& f_own, auto&& f_listed) {
         for (int lv = 0; lv < wave_clevels; ++lv) {
           if (oa.lv == lv) f_own(oa);
