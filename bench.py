@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=2, help="workload 0..4 (default 2 = L, 8192 envs x 256 steps)")
-    ap.add_argument("--cpu-envs", type=int, default=2048, help="environments of the CPU-oracle sample")
+    ap.add_argument("--cpu-envs", type=int, default=8192, help="environments of the CPU-oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain 256 MiB device copy, so "
                     "that a counter run has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg (flop model then uses "
