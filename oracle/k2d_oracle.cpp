@@ -156,8 +156,10 @@ struct Body {
 template <class R>
 struct Joint {
   int active = 0, a = 0, b = 0, fixed = 0, motor_on = 0;
+  int limited = 0;          // revolute only: the relative rotation theta_a - theta_b is kept in [limit_lo, limit_hi] (A.4.3)
   V2<R> anchor_a{0, 0}, anchor_b{0, 0};   // local frames of a and b
   R theta_f = 0, motor_speed = 0, motor_power = 0;
+  R limit_lo = 0, limit_hi = 0;
   V2<R> acc{0, 0};          // accumulated point impulse (on a)        (A.7)
   R acc_ang = 0;            // accumulated angular impulse, fixed only (A.7)
 };
@@ -420,6 +422,8 @@ struct JointRow {   // fixed for one substep
   R inv_det = 0;                 // 1 / its determinant
   V2<R> bias{0, 0};
   R ang_mass = 0, ang_bias = 0;
+  R lim_excess = 0;              // rotation beyond the upper (> 0) or the lower (< 0) limit; 0 = within limits
+  R lim_bias = 0;                // gamma * lim_excess
 };
 
 template <class R>
@@ -470,6 +474,20 @@ void solve_joint(Env<R>& E, Joint<R>& jt, const JointRow<R>& jr) {
     a.omega = a.omega + a.inv_inertia * d;
     b.omega = b.omega - b.inv_inertia * d;
     jt.acc_ang = jt.acc_ang + d;
+  }
+  if (!jt.fixed && jr.lim_excess != R(0) && jr.ang_mass > R(0)) {
+    // A.4.3: beyond a limit the angular impulse of a fixed joint (with the correction gamma * excess) is
+    // applied -- unless the relative angular velocity already brings the shapes back within the limits
+    // (so that a motor may return them faster than the correction would).  Not accumulated (A.7: warm
+    // starting joint limits is unstable).
+    R w = a.omega - b.omega;
+    bool restoring = (jr.lim_excess > R(0)) ? (w < R(0)) : (w > R(0));
+    if (!restoring) {
+      R d = -(w + jr.lim_bias) * jr.ang_mass;
+      a.omega = a.omega + a.inv_inertia * d;
+      b.omega = b.omega - b.inv_inertia * d;
+    }
+    E.min_margin = std::min(E.min_margin, std::fabs(double(w)));
   }
   // A.4.1: the two anchor points must have zero relative velocity; the velocity correction pulls
   // them back together.  Solved as a 2-D point constraint (the printed 1-D "collision along the
@@ -584,6 +602,14 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
     jr.ang_mass = (is > R(0)) ? R(1) / is : R(0);
     jr.ang_bias = R(P.gamma) * (a.theta - b.theta - jt.theta_f);
     if (!jt.fixed) jt.acc_ang = 0;
+    if (!jt.fixed && jt.limited) {   // A.4.3, decided once per substep like the collision manifolds
+      R rel = a.theta - b.theta;
+      if (rel > jt.limit_hi) jr.lim_excess = rel - jt.limit_hi;
+      else if (rel < jt.limit_lo) jr.lim_excess = rel - jt.limit_lo;
+      jr.lim_bias = R(P.gamma) * jr.lim_excess;
+      E.min_margin = std::min(E.min_margin, std::min(std::fabs(double(rel) - double(jt.limit_hi)),
+                                                     std::fabs(double(rel) - double(jt.limit_lo))));
+    }
   }
 
   // -- Apply motors (A.5): angular impulse p*tanh((w_a - w_b - s*A)*rho), read as a torque held
@@ -791,6 +817,9 @@ struct Batch : BatchBase {
     FIELD("joint_theta_f", J, e.joints[i].theta_f, RR)
     FIELD("joint_motor_speed", J, e.joints[i].motor_speed, RR)
     FIELD("joint_motor_power", J, e.joints[i].motor_power, RR)
+    FIELD("joint_limited", J, e.joints[i].limited, II)
+    FIELD("joint_limit_lo", J, e.joints[i].limit_lo, RR)
+    FIELD("joint_limit_hi", J, e.joints[i].limit_hi, RR)
     FIELD("joint_acc", J * 2, (i % 2 ? e.joints[i / 2].acc.y : e.joints[i / 2].acc.x), RR)
     FIELD("joint_acc_ang", J, e.joints[i].acc_ang, RR)
     FIELD("thruster_active", T, e.thrusters[i].active, II)

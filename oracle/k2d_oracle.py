@@ -24,6 +24,7 @@ SCENE_FIELDS = ["pos", "theta", "vel", "omega", "inv_mass", "inv_inertia", "fric
                 "joint_active", "joint_a", "joint_b", "joint_fixed", "joint_motor_on", "joint_anchor_a",
                 "joint_anchor_b", "joint_theta_f", "joint_motor_speed", "joint_motor_power",
                 "thruster_active", "thruster_body", "thruster_pos", "thruster_angle", "thruster_power"]
+OPTIONAL_FIELDS = ["joint_limited", "joint_limit_lo", "joint_limit_hi"]     # absent = no joint is limited
 ACC_FIELDS = ["joint_acc", "joint_acc_ang", "lambda_n", "lambda_t", "prev_active"]
 
 
@@ -138,6 +139,8 @@ class Oracle:
         rows = self.n_envs if env_ids is None else len(env_ids)
         for f in SCENE_FIELDS:
             self.set(f, scene[f], env_ids)
+        for f in OPTIONAL_FIELDS:
+            self.set(f, scene[f] if f in scene else np.zeros((rows, self.field_size(f))), env_ids)
         for f in ACC_FIELDS:
             if f in scene and not zero_acc:
                 self.set(f, scene[f], env_ids)

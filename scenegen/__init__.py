@@ -85,7 +85,7 @@ def empty_scene(caps, n_envs):
               n_verts=zi(P) + 4, verts=z(P, 4, 2), radius=z(C),
               joint_active=zi(J), joint_a=zi(J), joint_b=zi(J), joint_fixed=zi(J), joint_motor_on=zi(J),
               joint_anchor_a=z(J, 2), joint_anchor_b=z(J, 2), joint_theta_f=z(J), joint_motor_speed=z(J),
-              joint_motor_power=z(J),
+              joint_motor_power=z(J), joint_limited=zi(J), joint_limit_lo=z(J), joint_limit_hi=z(J),
               thruster_active=zi(T), thruster_body=zi(T), thruster_pos=z(T, 2), thruster_angle=z(T),
               thruster_power=z(T))
     if J:

@@ -70,7 +70,7 @@ class SceneBuilder:
         self._body(e, i, pos, theta, vel, omega, im[0], ii[0], friction, restitution, density, role)
         return i
 
-    def joint(self, a, b, world_anchor, fixed=False, motor_on=False, speed=0.0, power=0.0, e=0):
+    def joint(self, a, b, world_anchor, fixed=False, motor_on=False, speed=0.0, power=0.0, limits=None, e=0):
         q = self.n_joint[e]
         assert q < self.J
         self.n_joint[e] += 1
@@ -91,6 +91,9 @@ class SceneBuilder:
         s["joint_motor_on"][e, q] = int(motor_on)
         s["joint_motor_speed"][e, q] = speed
         s["joint_motor_power"][e, q] = power
+        if limits is not None:               # (lo, hi) of theta_a - theta_b
+            s["joint_limited"][e, q] = 1
+            s["joint_limit_lo"][e, q], s["joint_limit_hi"][e, q] = limits
         return q
 
     def thruster(self, body, local_pos, angle, power, e=0):

@@ -489,3 +489,113 @@ def test_table4_capacities_match_the_paper():
                 rows[k] = (int(s), int(m), int(l))
     for col, size in enumerate("SML"):
         assert scenegen.CAPS[size] == tuple(rows[k][col] for k in ("polygons", "circles", "joints", "thrusters"))
+
+
+# ------------------------------------------------------------------ joint limits (A.4.3)
+def _limited_pair(theta_a, omega_a, omega_b, limits, motor=None, gamma=None, n_iters=1):
+    """Two free boxes hinged at their common centre of mass (the point constraint then carries no torque),
+    no gravity: only the limit acts on the relative rotation theta_a - theta_b."""
+    caps = (2, 1, 1, 0)
+    sb = SceneBuilder(caps)
+    a = sb.box(0.4, 0.4, (0.0, 0.0), theta=theta_a, omega=omega_a)
+    b = sb.box(0.3, 0.3, (0.0, 0.0), omega=omega_b)
+    kw = dict(motor_on=True, speed=motor[0], power=motor[1]) if motor else {}
+    sb.joint(a, b, (0.0, 0.0), limits=limits, **kw)
+    kw = dict(gravity_y=0.0, n_iters=n_iters)
+    if gamma is not None:
+        kw["gamma"] = gamma
+    p = params(**kw)
+    o, sc = run(sb, p, caps=caps)
+    return o, sc, p, a, b
+
+
+def test_joint_limit_closed_form_beyond_the_upper_limit():
+    """Beyond the limit and still moving outwards: one visit leaves w_a - w_b = -gamma * excess (the fixed
+    joint's angular impulse with the excess in the place of the angle error); angular momentum is kept."""
+    o, sc, p, a, b = _limited_pair(0.6, 1.0, -0.5, (-0.5, 0.5))
+    Ia, Ib = 1 / sc["inv_inertia"][0, a], 1 / sc["inv_inertia"][0, b]
+    o.step(np.zeros((1, 1, 1)))
+    w = o.state()["omega"][0]
+    assert w[a] - w[b] == pytest.approx(-p["gamma"] * 0.1, rel=1e-9)
+    assert Ia * w[a] + Ib * w[b] == pytest.approx(Ia * 1.0 - Ib * 0.5, rel=1e-12)
+    # the impulse itself: j_r = (w_rel + gamma*excess) / (1/I_a + 1/I_b), taken from a, given to b
+    jr = (1.5 + p["gamma"] * 0.1) / (1 / Ia + 1 / Ib)
+    assert w[a] == pytest.approx(1.0 - jr / Ia, rel=1e-9) and w[b] == pytest.approx(-0.5 + jr / Ib, rel=1e-9)
+
+
+def test_joint_limit_mirror_symmetry_lower_limit():
+    o1, _, _, a, b = _limited_pair(0.6, 1.0, -0.5, (-0.5, 0.5))
+    o2, _, _, _, _ = _limited_pair(-0.6, -1.0, 0.5, (-0.5, 0.5))
+    o1.step(np.zeros((3, 1, 1))); o2.step(np.zeros((3, 1, 1)))
+    s1, s2 = o1.state(), o2.state()
+    assert np.allclose(s1["omega"], -s2["omega"], rtol=1e-12, atol=0)
+    assert np.allclose(s1["theta"], -s2["theta"], rtol=1e-12, atol=0)
+
+
+def test_joint_limit_leaves_restoring_motion_and_in_range_motion_alone():
+    # beyond the limit but already coming back: nothing is applied, however slowly it returns
+    o, _, _, a, b = _limited_pair(0.6, -0.01, 0.0, (-0.5, 0.5))
+    o.step(np.zeros((1, 1, 1)))
+    w = o.state()["omega"][0]
+    assert w[a] == -0.01 and w[b] == 0.0
+    # within the limits: free rotation whatever the speed
+    o, _, _, a, b = _limited_pair(0.2, 3.0, -1.0, (-0.5, 0.5))
+    o.step(np.zeros((1, 1, 1)))
+    w = o.state()["omega"][0]
+    assert w[a] == 3.0 and w[b] == -1.0
+    # a fixed joint ignores the limit fields, an unlimited joint too
+    caps = (2, 1, 1, 0)
+    sb = SceneBuilder(caps)
+    a = sb.box(0.4, 0.4, (0.0, 0.0), theta=0.6, omega=1.0)
+    b = sb.box(0.3, 0.3, (0.0, 0.0))
+    sb.joint(a, b, (0.0, 0.0))
+    o, _ = run(sb, params(gravity_y=0.0), caps=caps)
+    o.step(np.zeros((1, 1, 1)))
+    assert o.state()["omega"][0, a] == 1.0
+
+
+def test_joint_limit_motor_returns_faster_than_the_correction():
+    """A.4.3: the correction is withheld while the shapes are already returning, so a motor may bring them
+    back faster than gamma * excess would."""
+    g = 2.0
+    o, sc, p, a, b = _limited_pair(0.6, 0.0, 0.0, (-0.5, 0.5), motor=(4.0, 0.2), gamma=g, n_iters=4)
+    act = np.full((1, 1, 1), -1.0)          # motor target w_a - w_b = -4: back towards the range
+    o.step(act)
+    w = o.state()["omega"][0]
+    rel1 = w[a] - w[b]
+    assert rel1 < -g * 0.1                  # faster than the correction speed, and not slowed down to it
+    # without the motor the same start gives exactly the correction speed
+    o2, _, _, _, _ = _limited_pair(0.6, 0.0, 0.0, (-0.5, 0.5), gamma=g, n_iters=4)
+    o2.step(np.zeros((1, 1, 1)))
+    w2 = o2.state()["omega"][0]
+    assert w2[a] - w2[b] == pytest.approx(-g * 0.1, rel=1e-9)
+
+
+def test_limited_pendulum_stays_within_its_range():
+    """A bar hinged to a static block swings under gravity against a limit: the relative rotation never
+    leaves [lo, hi] by more than a small overshoot, and comes to rest at the limit."""
+    caps = (2, 1, 1, 0)
+    sb = SceneBuilder(caps)
+    top = sb.box(0.2, 0.2, (0.0, 2.0), static=True)
+    bar = sb.box(0.5, 0.05, (0.5, 2.0))                     # horizontal, hinged at its left end
+    sb.joint(top, bar, (0.0, 2.0), limits=(-0.1, 0.6))       # theta_top - theta_bar: the bar may drop 0.6 rad
+    p = params(n_substeps=2, n_iters=8)
+    o, sc = run(sb, p, caps=caps)
+    rel = []
+    for _ in range(600):
+        o.step(np.zeros((1, 1, 1)))
+        th = o.state()["theta"][0]
+        rel.append(th[top] - th[bar])
+    rel = np.array(rel)
+    assert rel.max() < 0.6 + 0.05 and rel.min() > -0.1 - 0.05     # at most one substep of travel at impact speed
+    assert rel.max() > 0.55                                  # it did reach the limit
+    assert abs(rel[-1] - 0.6) < 0.02 and abs(o.state()["omega"][0, bar]) < 0.05
+    # without the limit the same bar swings far past it
+    sb2 = SceneBuilder(caps)
+    top = sb2.box(0.2, 0.2, (0.0, 2.0), static=True)
+    bar = sb2.box(0.5, 0.05, (0.5, 2.0))
+    sb2.joint(top, bar, (0.0, 2.0))
+    o2, _ = run(sb2, p, caps=caps)
+    o2.step(np.zeros((60, 1, 1)))
+    th = o2.state()["theta"][0]
+    assert th[top] - th[bar] > 1.0
