@@ -66,8 +66,10 @@ typedef struct {
  *   per polygon (P entries each):  n_verts(i) in {3,4};  verts: 8 arrays [P], array 2*v+c holds
  *     coordinate c of local vertex v (counter-clockwise, centred on the centre of mass)
  *   per circle (C): radius
- *   per joint (J): joint_flags(i): bit0 active, bit1 fixed, bit2 motor on;  joint_a(i) joint_b(i) shape indices;
+ *   per joint (J): joint_flags(i): bit0 active, bit1 fixed, bit2 motor on, bit4 limited (revolute joints
+ *     only, A.4.3);  joint_a(i) joint_b(i) shape indices;
  *     anchor_a_x anchor_a_y anchor_b_x anchor_b_y (local frames); theta_f; motor_speed; motor_power;
+ *     limit_lo limit_hi (range of theta_a - theta_b of a limited joint);
  *     acc_x acc_y (accumulated point impulse, A.7); acc_ang (accumulated angular impulse of a fixed joint)
  *   per thruster (T): thr_flags(i): bit0 active; thr_body(i); pos_x pos_y (local); angle; power
  *   -- end of scene description --
@@ -82,7 +84,7 @@ typedef struct {
       shape_flags;
   int32_t n_verts, verts, radius;
   int32_t joint_flags, joint_a, joint_b, anchor_a_x, anchor_a_y, anchor_b_x, anchor_b_y, theta_f, motor_speed,
-      motor_power, acc_x, acc_y, acc_ang;
+      motor_power, limit_lo, limit_hi, acc_x, acc_y, acc_ang;
   int32_t thr_flags, thr_body, thr_pos_x, thr_pos_y, thr_angle, thr_power;
   int32_t scene_words;
   int32_t lambda, pair_state;

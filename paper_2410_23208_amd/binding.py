@@ -32,7 +32,7 @@ class k2d_params(ctypes.Structure):
 _LAYOUT_FIELDS = ["n_shapes", "n_pairs", "pos_x", "pos_y", "theta", "vel_x", "vel_y", "omega", "inv_mass",
                   "inv_inertia", "friction", "restitution", "density", "shape_flags", "n_verts", "verts", "radius",
                   "joint_flags", "joint_a", "joint_b", "anchor_a_x", "anchor_a_y", "anchor_b_x", "anchor_b_y",
-                  "theta_f", "motor_speed", "motor_power", "acc_x", "acc_y", "acc_ang", "thr_flags", "thr_body",
+                  "theta_f", "motor_speed", "motor_power", "limit_lo", "limit_hi", "acc_x", "acc_y", "acc_ang", "thr_flags", "thr_body",
                   "thr_pos_x", "thr_pos_y", "thr_angle", "thr_power", "scene_words", "lambda", "pair_state",
                   "state_words", "obs_dim"]
 
@@ -131,6 +131,9 @@ def pack_scenes(caps, scene):
     jf = ((np.asarray(scene["joint_active"]) != 0).astype(np.int32) |
           ((np.asarray(scene["joint_fixed"]) != 0).astype(np.int32) << 1) |
           ((np.asarray(scene["joint_motor_on"]) != 0).astype(np.int32) << 2))
+    if "joint_limited" in scene:
+        jf = jf | ((np.asarray(scene["joint_limited"]) != 0).astype(np.int32) << 4)
+        putf(L["limit_lo"], scene["joint_limit_lo"]); putf(L["limit_hi"], scene["joint_limit_hi"])
     puti(L["joint_flags"], jf); puti(L["joint_a"], scene["joint_a"]); puti(L["joint_b"], scene["joint_b"])
     aa = np.asarray(scene["joint_anchor_a"]).reshape(n, J, 2)
     ab = np.asarray(scene["joint_anchor_b"]).reshape(n, J, 2)

@@ -74,6 +74,8 @@ constexpr k2d_layout make_layout(int P, int C, int J, int T) {
   L.theta_f = o; o += J;
   L.motor_speed = o; o += J;
   L.motor_power = o; o += J;
+  L.limit_lo = o; o += J;
+  L.limit_hi = o; o += J;
   L.acc_x = o; o += J;
   L.acc_y = o; o += J;
   L.acc_ang = o; o += J;
@@ -625,7 +627,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
   }
   wave_sync();
   // joints: lane j of the group owns joint j for the whole launch
-  bool j_live = false, j_fixed = false, j_motor = false;
+  bool j_live = false, j_fixed = false, j_motor = false, j_limited = false;
   int ja = 0, jb = 0;
   float j_aax = 0.f, j_aay = 0.f, j_abx = 0.f, j_aby = 0.f, j_thf = 0.f, j_speed = 0.f, j_power = 0.f;
   float j_accx = 0.f, j_accy = 0.f, j_acca = 0.f;
@@ -637,6 +639,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     if (!idx_ok) { ja = 0; jb = 0; }
     j_fixed = (fl >> 1) & 1;
     j_motor = (fl >> 2) & 1;
+    j_limited = ((fl >> 4) & 1) && !j_fixed;
     j_live = (fl & 1) && idx_ok && (f2i(E[L.shape_flags + ja]) & 1) && (f2i(E[L.shape_flags + jb]) & 1) &&
              (E[L.inv_mass + ja] + E[L.inv_mass + jb]) > 0.f;
     j_aax = E[L.anchor_a_x + k]; j_aay = E[L.anchor_a_y + k];
@@ -649,7 +652,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       atomicOr(reinterpret_cast<unsigned*>(E + K::X_JOINED + ja), 1u << jb);
       atomicOr(reinterpret_cast<unsigned*>(E + K::X_JOINED + jb), 1u << ja);
     }
-    E[L.joint_flags + k] = i2f((fl & 7) | (j_live ? 8 : 0));
+    E[L.joint_flags + k] = i2f((fl & 23) | (j_live ? 8 : 0));
   }
   wave_sync();
   // Shapes that no impulse can move (no inverse mass, no inverse inertia; inactive ones too).  An
@@ -792,7 +795,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
 
       // ---- joint constants of this substep; motor and thruster impulses from the same velocities ----
       float j_rax = 0.f, j_ray = 0.f, j_rbx = 0.f, j_rby = 0.f, j_k11 = 0.f, j_k12 = 0.f, j_k22 = 0.f;
-      float j_idet = 0.f, j_bx = 0.f, j_by = 0.f, j_angm = 0.f, j_angb = 0.f, motor = 0.f;
+      float j_idet = 0.f, j_bx = 0.f, j_by = 0.f, j_angm = 0.f, j_angb = 0.f, j_exc = 0.f, motor = 0.f;
       float j_ima = 0.f, j_iia = 0.f, j_imb = 0.f, j_iib = 0.f;
       if (k < J && j_live) {
         if (!prm.warm_start) { j_accx = 0.f; j_accy = 0.f; j_acca = 0.f; }
@@ -812,6 +815,13 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         float is = j_iia + j_iib;
         j_angm = (is > 0.f) ? 1.f / is : 0.f;
         j_angb = prm.gamma * (E[L.theta + ja] - E[L.theta + jb] - j_thf);
+        if (j_limited) {   // A.4.3: rotation beyond a limit, decided once per substep
+          const float rel = E[L.theta + ja] - E[L.theta + jb];
+          const float lo = E[L.limit_lo + k], hi = E[L.limit_hi + k];
+          if (rel > hi) j_exc = rel - hi;
+          else if (rel < lo) j_exc = rel - lo;
+          j_angb = prm.gamma * j_exc;
+        }
         if (!j_fixed && j_motor) {   // A.5
           float arg = (E[L.omega + ja] - E[L.omega + jb] - j_speed * act_m) * prm.rho;
           motor = j_power * k2d_tanh(arg) * h;
@@ -1068,6 +1078,15 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
               wa = wa + j_iia * d;
               wb = wb - j_iib * d;
               j_acca = j_acca + d;
+            }
+            if (!j_fixed && j_exc != 0.f && j_angm > 0.f) {   // A.4.3: not while already coming back, never accumulated
+              const float w = wa - wb;
+              const bool restoring = (j_exc > 0.f) ? (w < 0.f) : (w > 0.f);
+              if (!restoring) {
+                float d = -(w + j_angb) * j_angm;
+                wa = wa + j_iia * d;
+                wb = wb - j_iib * d;
+              }
             }
             float cx, cy;   // A.4.1: point constraint, 2x2 solve
             S::rel_vel(vax, vay, wa, j_rax, j_ray, vbx, vby, wb, j_rbx, j_rby, cx, cy);

@@ -101,6 +101,18 @@ def to_f32(scene):
     return out
 
 
+def add_joint_limits(scene, seed=SEED, width=(0.05, 0.5)):
+    """Variant of a generated scene in which every revolute joint is limited (A.4.3): the relative rotation
+    theta_a - theta_b may leave its initial value by U[width] radians either way.  Returns a new dict."""
+    sc = {k: v.copy() for k, v in scene.items()}
+    rng = np.random.default_rng(seed)
+    shape = sc["joint_theta_f"].shape
+    sc["joint_limited"] = (np.asarray(sc["joint_fixed"]) == 0).astype(np.int64)
+    sc["joint_limit_lo"] = sc["joint_theta_f"] - rng.uniform(width[0], width[1], shape)
+    sc["joint_limit_hi"] = sc["joint_theta_f"] + rng.uniform(width[0], width[1], shape)
+    return to_f32(sc)
+
+
 def select_envs(scene, ids):
     return {k: v[ids] for k, v in scene.items()}
 

@@ -32,7 +32,7 @@ def test_layout_matches_header_and_table4():
         L = k2d.get_layout(caps)
         P, C, J, T = caps
         assert L["n_shapes"] == P + C and L["n_pairs"] == n_pairs
-        assert L["scene_words"] == 12 * (P + C) + 9 * P + C + 13 * J + 6 * T
+        assert L["scene_words"] == 12 * (P + C) + 9 * P + C + 15 * J + 6 * T
         assert L["lambda"] % 4 == 0 and L["state_words"] == L["pair_state"] + (n_pairs + 3) // 4
         assert L["obs_dim"] == 23 * P + 15 * C + 11 * J + 6 * T
         assert k2d.state_bytes(caps, 10) >= 10 * 4 * L["state_words"]

@@ -185,6 +185,45 @@ def test_triangles_circles_inside_polygons_and_static_joints():
     _hand_scene_parity(sb, mkparams(n_substeps=2, n_iters=8), 40)
 
 
+def test_joint_limits_hand_scene():
+    """A.4.3: a bar hinged to a static block drops against its limit; a motorised limited hinge in free space."""
+    caps = scenegen.CAPS["M"]
+    sb = SceneBuilder(caps)
+    top = sb.box(0.2, 0.2, (0.0, 2.0), static=True)
+    bar = sb.box(0.5, 0.05, (0.5, 2.0))
+    a = sb.box(0.4, 0.3, (3.0, 3.0), omega=2.0)
+    b = sb.box(0.3, 0.2, (3.3, 3.0))
+    sb.box(5.0, 0.1, (0, 0), static=True)
+    sb.joint(top, bar, (0.0, 2.0), limits=(-0.1, 0.6))
+    sb.joint(a, b, (3.2, 3.0), motor_on=True, speed=2.0, power=0.3, limits=(-0.3, 0.2))
+    prm = mkparams(n_substeps=2, n_iters=8)
+    sc = sb.scene()
+    act = scenegen.make_actions(1, 90, 1)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b_ = parity.run_gpu(caps, prm, sc, act)
+    gs, os_ = b_.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    th = os_["theta"][0]
+    assert -0.15 < th[top] - th[bar] < 0.65               # the bar stays within its range
+
+
+@pytest.mark.parametrize("cfg,steps", [(2, 48), (4, 64)])
+def test_joint_limits_generated_scenes(cfg, steps):
+    """The generated workloads with every revolute joint limited: bit-identical, and the limits matter."""
+    n = SMALL[cfg]
+    caps, prm, sc0 = scenegen.make_scene(cfg, n_envs=n)
+    sc = scenegen.add_joint_limits(sc0)
+    act = scenegen.make_actions(cfg, steps, n)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b = parity.run_gpu(caps, prm, sc, act)
+    gs, os_ = b.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    free = parity.run_oracle(caps, prm, sc0, act).state()
+    assert (np.abs(free["theta"] - os_["theta"]).max(1) > 1e-3).mean() > 0.2
+
+
 # ------------------------------------------------------------------------- full sizes, sampled outputs
 @pytest.mark.parametrize("cfg,steps,n_sample", [(0, 200, 64), (1, 256, 128), (2, 256, 192), (3, 128, 96),
                                                 (4, 256, 128)])
