@@ -311,24 +311,24 @@ struct Step {
     float best_d2 = INFINITY, qx = 0.f, qy = 0.f;
     float smax = -INFINITY, snx = 0.f, sny = 0.f;
     float2 v = wv(E, 0, pa);
+    // (vertex slot 3 of a triangle repeats vertex 0; its fourth "edge" is computed and thrown away, so
+    // that the loop has no branch)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (i < na) {
-        int i1 = (i + 1 == na) ? 0 : i + 1;
-        float2 v1 = wv(E, i1, pa);
-        float2 nr = wn(E, i, pa);
-        float ex = v1.x - v.x, ey = v1.y - v.y;
-        float rx = cx - v.x, ry = cy - v.y;
-        float t = dot2(rx, ry, ex, ey) / dot2(ex, ey, ex, ey);
-        t = fminf(fmaxf(t, 0.f), 1.f);
-        float qix = v.x + t * ex, qiy = v.y + t * ey;
-        float dqx = cx - qix, dqy = cy - qiy;
-        float d2 = dot2(dqx, dqy, dqx, dqy);
-        if (d2 < best_d2) { best_d2 = d2; qx = qix; qy = qiy; }
-        float s = dot2(nr.x, nr.y, rx, ry);
-        if (s > smax) { smax = s; snx = nr.x; sny = nr.y; }
-        v = v1;
-      }
+      const bool real = i < 3 || na == 4;
+      float2 v1 = wv(E, (i + 1) & 3, pa);
+      float2 nr = wn(E, i, pa);
+      float ex = v1.x - v.x, ey = v1.y - v.y;
+      float rx = cx - v.x, ry = cy - v.y;
+      float t = dot2(rx, ry, ex, ey) / dot2(ex, ey, ex, ey);
+      t = fminf(fmaxf(t, 0.f), 1.f);
+      float qix = v.x + t * ex, qiy = v.y + t * ey;
+      float dqx = cx - qix, dqy = cy - qiy;
+      float d2 = dot2(dqx, dqy, dqx, dqy);
+      if (real && d2 < best_d2) { best_d2 = d2; qx = qix; qy = qiy; }
+      float s = dot2(nr.x, nr.y, rx, ry);
+      if (real && s > smax) { smax = s; snx = nr.x; sny = nr.y; }
+      v = v1;
     }
     if (smax <= 0.f) {   // centre inside the polygon: the face of largest signed distance
       m.nx = snx; m.ny = sny;
@@ -350,21 +350,19 @@ struct Step {
                                                     float& best, int& idx) {
     best = -INFINITY;
     idx = 0;
+    // (vertex slot 3 of a triangle repeats vertex 0, which leaves the minimum over Y's vertices as it is;
+    // the fourth "face" of a triangle X is computed and thrown away: no branch in the loops)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (i < nx_) {
-        float2 nr = wn(E, i, px);
-        float2 w = wv(E, i, px);
-        float smin = INFINITY;
+      float2 nr = wn(E, i, px);
+      float2 w = wv(E, i, px);
+      float smin = INFINITY;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          if (k < ny_) {
-            float s = dot2(nr.x, nr.y, yw[k].x - w.x, yw[k].y - w.y);
-            smin = (s < smin) ? s : smin;
-          }
-        }
-        if (smin > best) { best = smin; idx = i; }
+      for (int k = 0; k < 4; ++k) {
+        float s = dot2(nr.x, nr.y, yw[k].x - w.x, yw[k].y - w.y);
+        smin = (s < smin) ? s : smin;
       }
+      if ((i < 3 || nx_ == 4) && smin > best) { best = smin; idx = i; }
     }
   }
 
@@ -389,11 +387,9 @@ struct Step {
     float dmin = INFINITY;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      if (j < ni) {
-        float2 nj = wn(E, j, pi);
-        float d = dot2(nj.x, nj.y, nref.x, nref.y);
-        if (d < dmin) { dmin = d; jinc = j; }
-      }
+      float2 nj = wn(E, j, pi);
+      float d = dot2(nj.x, nj.y, nref.x, nref.y);
+      if ((j < 3 || ni == 4) && d < dmin) { dmin = d; jinc = j; }
     }
     float2 v0 = wv(E, jinc, pi);
     float2 v1 = wv(E, (jinc + 1 == ni) ? 0 : jinc + 1, pi);
@@ -781,6 +777,8 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
             wx[v] = px + fmaf(cs, lx, -(sn * ly));
             wy[v] = py + fmaf(sn, lx, cs * ly);
           }
+          if (nv == 3) { wx[3] = wx[0]; wy[3] = wy[0]; }   // a triangle's spare slot repeats vertex 0: the
+                                                           // manifold code can then run over four vertices
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             int v1 = (v + 1 == nv) ? 0 : ((v + 1) & 3);
