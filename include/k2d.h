@@ -121,6 +121,16 @@ int k2d_reset(k2d_batch* batch, const void* scenes_dev, const int32_t* env_ids_d
  * n_envs must equal the batch's. */
 int k2d_step(k2d_batch* batch, const float* actions_dev, int n_envs, int n_steps, void* stream);
 
+/* k2d_step with new episodes started inside the launch (training runs every environment on levels sampled
+ * anew whenever an episode ends, Sec. 4; Appendix B times the engine over whole rollouts): after step s
+ * (0-based) every environment e with reset_level_dev[s * n_envs + e] = l, 0 <= l < n_levels, is
+ * re-initialised from record l of levels_dev exactly as k2d_reset would do it (scene description copied,
+ * joint and contact accumulators and pair states zeroed); other values (-1) leave the environment alone.
+ * levels_dev: n_levels records of `scene_words` words (the layout k2d_reset consumes), device memory;
+ * reset_level_dev: int32 [n_steps][n_envs], device memory.  Both must stay valid until the launch has run. */
+int k2d_step_reset(k2d_batch* batch, const float* actions_dev, int n_envs, int n_steps, const void* levels_dev,
+                   int n_levels, const int32_t* reset_level_dev, void* stream);
+
 /* Flat symbolic observation (the physical entries of Tables 5-7), float [n_envs][obs_dim]; per polygon:
  * pos 2, vel 2, inv_mass, inv_inertia, density, tanh(omega/10), sin theta, cos theta, friction, restitution,
  * vertices 8, n_verts, active, role (23); per circle the same 12 then radius, active, role (15); per joint:

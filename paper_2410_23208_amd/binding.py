@@ -59,6 +59,7 @@ def lib():
         L.k2d_free_batch.argtypes = [vp]
         L.k2d_reset.argtypes = [vp, vp, vp, i32, vp]
         L.k2d_step.argtypes = [vp, vp, i32, i32, vp]
+        L.k2d_step_reset.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp]
         L.k2d_read_obs.argtypes = [vp, vp, vp]
         L.k2d_read_contacts.argtypes = [vp, vp, vp, vp]
         L.k2d_read_state.argtypes = [vp, vp, vp]
@@ -68,6 +69,7 @@ def lib():
 
 
 EXPORTS = ["k2d_get_layout", "k2d_state_bytes", "k2d_alloc_batch", "k2d_free_batch", "k2d_reset", "k2d_step",
+           "k2d_step_reset",
            "k2d_read_obs", "k2d_read_contacts", "k2d_read_state", "k2d_write_state"]
 
 
@@ -235,6 +237,22 @@ class Batch:
         assert actions.is_cuda and actions.dtype == self.torch.float32 and actions.is_contiguous()
         assert actions.numel() >= n_steps * self.n_envs * (self.J + self.T)
         _check(lib().k2d_step(self._h, actions.data_ptr(), self.n_envs, int(n_steps), self._stream()), "k2d_step")
+
+    def step_reset(self, actions, levels, reset_level, n_steps=None):
+        """k2d_step with episodes restarted inside the launch.  levels: device int32/float32 words
+        [n_levels, scene_words] (pack_scenes); reset_level: device int32 [n_steps, n_envs], -1 = no reset."""
+        torch = self.torch
+        if n_steps is None:
+            n_steps = actions.shape[0]
+        assert actions.is_cuda and actions.dtype == torch.float32 and actions.is_contiguous()
+        assert actions.numel() >= n_steps * self.n_envs * (self.J + self.T)
+        assert levels.is_cuda and levels.is_contiguous() and levels.element_size() == 4
+        assert levels.dim() == 2 and levels.shape[1] == self.layout["scene_words"]
+        assert reset_level.is_cuda and reset_level.dtype == torch.int32 and reset_level.is_contiguous()
+        assert reset_level.numel() >= n_steps * self.n_envs
+        _check(lib().k2d_step_reset(self._h, actions.data_ptr(), self.n_envs, int(n_steps), levels.data_ptr(),
+                                    int(levels.shape[0]), reset_level.data_ptr(), self._stream()), "k2d_step_reset")
+        self._keep = (levels, reset_level, actions)
 
     def read_obs(self):
         obs = self.torch.empty((self.n_envs, self.layout["obs_dim"]), dtype=self.torch.float32, device=self.device)

@@ -572,9 +572,13 @@ struct Step {
   }
 };
 
-template <class K>
+// RESET: after step s an environment e with reset_level[s * n_envs + e] = l >= 0 starts a new episode from
+// record l of `levels` (what k2d_reset does between launches, without leaving the kernel).
+template <class K, bool RESET>
 __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ state, const float* __restrict__ actions,
-                                                      int n_envs, int n_steps, Params prm) {
+                                                      int n_envs, int n_steps, Params prm,
+                                                      const float* __restrict__ levels, int n_level_records,
+                                                      const int32_t* __restrict__ reset_level) {
   using S = Step<K>;
   constexpr k2d_layout L = K::L;
   constexpr int N = K::N, P = K::P, J = K::J, T = K::T, G = K::G, R = K::R, GP = K::GP, H = K::H;
@@ -600,8 +604,14 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     }
   }
   wave_sync();
+  unsigned my_r = 0u;   // the rounds this lane takes
+  for (int r = 0; r < R; ++r)
+    if (r % H == rpar) my_r |= 1u << r;
 
-  // ---- per-launch derived data ----
+  int step = 0;
+  bool first = true;
+  do {   // (one pass, unless environments are re-initialised on the way)
+  // ---- derived data: per launch, and again after environments of the wavefront started a new episode ----
   for (int i = k; i < N; i += G) {
     float sn, cs;
     k2d_sincos(E[L.theta + i], sn, cs);
@@ -703,12 +713,9 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
   unsigned char* pstate = reinterpret_cast<unsigned char*>(E + K::X_PSTATE);
   unsigned* bitmap = reinterpret_cast<unsigned*>(E + K::X_BITMAP);
   unsigned elig = 0u, pp_mask = 0u, pc_mask = 0u;
-  if (k < GP)
+  if (k < GP && first)
     for (int r = 0; r < 16; ++r) pstate[k * 16 + r] = 0;
   wave_sync();
-  unsigned my_r = 0u;   // the rounds this lane takes
-  for (int r = 0; r < R; ++r)
-    if (r % H == rpar) my_r |= 1u << r;
   unsigned long long my_ab = 0ull;   // this lane's pairs, a | b << 4, eight bits for each of its rounds
   for (int r = 0; r < R; ++r) {
     int a, b;
@@ -720,7 +727,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
                 !((f2i(E[K::X_JOINED + a]) >> b) & 1) && (E[L.inv_mass + a] + E[L.inv_mass + b]) > 0.f;
       if (ok) {
         elig |= 1u << r;
-        if (env_ok) {
+        if (first && env_ok) {
           const unsigned char* ps = reinterpret_cast<const unsigned char*>(Rg + L.pair_state);
           pstate[kp * 16 + r] = ps[S::pair_index(a, b)] & 3;
         }
@@ -753,7 +760,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
   const float h = prm.h;
   const int A = J + T;
 
-  for (int step = 0; step < n_steps; ++step) {
+  for (; step < n_steps; ++step) {
     float act_m = 0.f, act_t = 0.f;
     if (env_ok) {
       const float* ap = actions + ((size_t)step * n_envs + env) * A;
@@ -1181,15 +1188,38 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         wave_sync();
       }
     }
+    if (RESET) {   // new episodes (wave-uniform branch: the wavefront leaves the step loop together)
+      int rl = env_ok ? reset_level[(size_t)step * n_envs + env] : -1;
+      if (rl >= n_level_records) rl = -1;
+      if (__any(rl >= 0)) {
+        if (rl >= 0) {
+          const float* src = levels + (size_t)rl * L.scene_words;
+          for (int w = k; w < L.scene_words; w += G) {
+            float v = src[w];
+            if (w >= L.acc_x && w < L.thr_flags) v = 0.f;   // accumulated joint impulses start at zero
+            E[w] = v;
+            Rg[w] = v;
+          }
+          j_accx = 0.f; j_accy = 0.f; j_acca = 0.f;
+          if (k < GP)   // no collision is carried into the new episode
+            for (int r = 0; r < 16; ++r) pstate[k * 16 + r] = 0;
+        }
+        ++step;
+        break;
+      }
+    }
   }
-
-  // ---- write back: dynamic shape state, joint accumulators, pair states ----
+  // the joint accumulators return to the LDS image (from where a new pass, or the write-back, takes them)
   if (k < J) {
     E[L.acc_x + k] = j_accx;
     E[L.acc_y + k] = j_accy;
     E[L.acc_ang + k] = j_acca;
   }
   wave_sync();
+  first = false;
+  } while (RESET && step < n_steps);
+
+  // ---- write back: dynamic shape state, joint accumulators, pair states ----
   for (int e = 0; e < K::EPW; ++e) {
     if (env0 + e < n_envs) {
       const float* src = lds + e * K::LDS_STRIDE;
@@ -1200,6 +1230,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
   }
   if (env_ok) {
     unsigned char* ps = reinterpret_cast<unsigned char*>(Rg + L.pair_state);
+    const unsigned char* pstate = reinterpret_cast<const unsigned char*>(E + K::X_PSTATE);
     for (int r = 0; r < R; ++r) {
       int a, b;
       if (((my_r >> r) & 1u) && S::sched_pair(r, kp, a, b)) ps[S::pair_index(a, b)] = pstate[kp * 16 + r];
@@ -1347,17 +1378,19 @@ int caps_class(const k2d_caps* c) {
 }
 int rec_words_of(int cls) { return cls == 0 ? CfgS::REC_WORDS : cls == 1 ? CfgM::REC_WORDS : CfgL::REC_WORDS; }
 
-template <class K>
-int launch_step(float* state, const float* actions, int n_envs, int n_steps, const Params& prm, hipStream_t st) {
+template <class K, bool RESET>
+int launch_step(float* state, const float* actions, int n_envs, int n_steps, const Params& prm, const float* levels,
+                int n_levels, const int32_t* reset_level, hipStream_t st) {
   static bool attr_done = false;
   if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k2d_step_kernel<K>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k2d_step_kernel<K, RESET>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, K::LDS_BYTES) != hipSuccess)
       return K2D_E_HIP;
     attr_done = true;
   }
   int grid = (n_envs + K::EPW - 1) / K::EPW;
-  hipLaunchKernelGGL(k2d_step_kernel<K>, dim3(grid), dim3(64), K::LDS_BYTES, st, state, actions, n_envs, n_steps, prm);
+  hipLaunchKernelGGL((k2d_step_kernel<K, RESET>), dim3(grid), dim3(64), K::LDS_BYTES, st, state, actions, n_envs,
+                     n_steps, prm, levels, n_levels, reset_level);
   return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
 }
 
@@ -1422,10 +1455,7 @@ int k2d_reset(k2d_batch* b, const void* scenes_dev, const int32_t* env_ids_dev, 
   return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
 }
 
-int k2d_step(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, void* stream) {
-  if (!b || !actions_dev || n_steps < 1) return K2D_E_ARG;
-  if (n_envs != b->n_envs) return K2D_E_SIZE;
-  const k2d_params& p = b->params;
+static Params device_params(const k2d_params& p) {
   Params prm;
   prm.h = p.dt / (float)p.n_substeps;
   prm.gravity_y = p.gravity_y;
@@ -1436,11 +1466,32 @@ int k2d_step(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, vo
   prm.rest_thr = p.restitution_threshold;
   prm.clip_thr = p.clip_thruster_01;
   prm.joint_alpha = p.joint_alpha; prm.joint_beta = p.joint_beta; prm.tie_eps = p.tie_eps;
+  return prm;
+}
+
+int k2d_step(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, void* stream) {
+  if (!b || !actions_dev || n_steps < 1) return K2D_E_ARG;
+  if (n_envs != b->n_envs) return K2D_E_SIZE;
+  const Params prm = device_params(b->params);
   hipStream_t st = static_cast<hipStream_t>(stream);
   switch (b->cls) {
-    case 0: return launch_step<CfgS>(b->state, actions_dev, n_envs, n_steps, prm, st);
-    case 1: return launch_step<CfgM>(b->state, actions_dev, n_envs, n_steps, prm, st);
-    default: return launch_step<CfgL>(b->state, actions_dev, n_envs, n_steps, prm, st);
+    case 0: return launch_step<CfgS, false>(b->state, actions_dev, n_envs, n_steps, prm, nullptr, 0, nullptr, st);
+    case 1: return launch_step<CfgM, false>(b->state, actions_dev, n_envs, n_steps, prm, nullptr, 0, nullptr, st);
+    default: return launch_step<CfgL, false>(b->state, actions_dev, n_envs, n_steps, prm, nullptr, 0, nullptr, st);
+  }
+}
+
+int k2d_step_reset(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, const void* levels_dev,
+                   int n_levels, const int32_t* reset_level_dev, void* stream) {
+  if (!b || !actions_dev || n_steps < 1 || !levels_dev || n_levels < 1 || !reset_level_dev) return K2D_E_ARG;
+  if (n_envs != b->n_envs) return K2D_E_SIZE;
+  const Params prm = device_params(b->params);
+  const float* lv = static_cast<const float*>(levels_dev);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  switch (b->cls) {
+    case 0: return launch_step<CfgS, true>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, st);
+    case 1: return launch_step<CfgM, true>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, st);
+    default: return launch_step<CfgL, true>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, st);
   }
 }
 

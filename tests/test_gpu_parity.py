@@ -122,6 +122,52 @@ def test_heterogeneous_batch_with_resets():
         assert np.array_equal(gs[k], os_[k]), k
 
 
+@pytest.mark.parametrize("cfg,n,steps", [(4, 195, 24), (1, 131, 30), (0, 67, 20)])
+def test_resets_inside_one_launch(cfg, n, steps):
+    """k2d_step_reset: the protocol of the heterogeneous workload (a seeded 5 % of the environments restart
+    from new scenes after every step) in ONE launch, against the oracle stepped and reloaded from the host,
+    and against the GPU path that alternates k2d_step(1) and k2d_reset."""
+    import torch
+    import paper_2410_23208_amd as k2d
+    from oracle.k2d_oracle import Oracle
+    caps, prm, sc = scenegen.make_scene(cfg, n_envs=n)
+    act = scenegen.make_actions(cfg, steps, n)
+    o = Oracle(caps, n, prm, "f32")
+    o.load_scene(sc)
+    alt = k2d.Batch(caps, n, prm)
+    alt.reset(k2d.pack_scenes(caps, sc))
+    act_d = torch.from_numpy(act).cuda()
+    levels, sched = [], np.full((steps, n), -1, dtype=np.int32)
+    for s in range(steps):
+        o.step(act[s:s + 1])
+        alt.step(act_d[s:s + 1].contiguous())
+        ids = scenegen.reset_ids(cfg, s, n, frac=0.08)
+        if len(ids):
+            _, _, fresh = scenegen.make_scene(cfg, env_ids=ids, episode=s + 1)
+            o.load_scene(fresh, env_ids=ids)
+            alt.reset(k2d.pack_scenes(caps, fresh), env_ids=ids)
+            words = k2d.pack_scenes(caps, fresh)
+            sched[s, ids] = np.arange(len(levels), len(levels) + len(ids))
+            levels.extend(list(words))
+    assert len(levels) > steps
+    one = k2d.Batch(caps, n, prm)
+    one.reset(k2d.pack_scenes(caps, sc))
+    lv = torch.from_numpy(np.stack(levels).view(np.int32)).cuda()
+    one.step_reset(act_d, lv, torch.from_numpy(sched).cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(one.read_state(), alt.read_state())
+    gs, os_ = one.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    # the static description of a restarted environment is the new level's (next launch starts from it)
+    more = scenegen.make_actions(cfg, 4, n)
+    o.step(more)
+    one.step(torch.from_numpy(more).cuda())
+    gs, os_ = one.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+
+
 # ------------------------------------------------------------------------------------------ edge cases
 def _hand_scene_parity(sb, prm, steps, n_envs=1):
     sc = sb.scene()
