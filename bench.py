@@ -69,13 +69,27 @@ def main():
     words = torch.from_numpy(k2d.pack_scenes(caps, scene).view(np.int32)).to(dev)
     actions = torch.from_numpy(actions_h).to(dev)
     batch = k2d.Batch(caps, n_envs, params)
+    # workload 4: after every step a seeded 5 % of the environments start a new episode (inside the launch,
+    # from a device-resident pool that holds one fresh scene per environment)
+    restarts = args.config == 4
+    if restarts:
+        _, _, fresh = scenegen.make_scene(args.config, episode=1)
+        pool = torch.from_numpy(k2d.pack_scenes(caps, fresh).view(np.int32)).to(dev)
+        sched_h = np.full((n_steps, n_envs), -1, dtype=np.int32)
+        for s in range(n_steps):
+            ids = scenegen.reset_ids(args.config, s, n_envs)
+            sched_h[s, ids] = ids
+        sched = torch.from_numpy(sched_h).to(dev)
     torch.cuda.synchronize()
 
     def one_pass(ev=None):
         batch.reset(words)
         if ev:
             ev[0].record()
-        batch.step(actions, n_steps)
+        if restarts:
+            batch.step_reset(actions, pool, sched, n_steps)
+        else:
+            batch.step(actions, n_steps)
         if ev:
             ev[1].record()
 
@@ -106,7 +120,15 @@ def main():
     ora = Oracle(caps, ns, params, "f32")
     ora.load_scene(sub)
     t1 = time.perf_counter()
-    ora.step(actions_h[:, :ns], n_threads=cores)
+    if restarts:
+        for s in range(n_steps):
+            ora.step(actions_h[s:s + 1, :ns], n_threads=cores)
+            ids = scenegen.reset_ids(args.config, s, n_envs)
+            ids = ids[ids < ns]
+            if len(ids):
+                ora.load_scene(scenegen.select_envs(fresh, ids), env_ids=ids)
+    else:
+        ora.step(actions_h[:, :ns], n_threads=cores)
     cpu_t = time.perf_counter() - t1
     nsub = ora.get("substeps_done").sum()
     slots = ora.get("active_slots_sum").sum() / nsub
