@@ -143,6 +143,21 @@ int k2d_read_obs(k2d_batch* batch, float* obs_dev, void* stream);
  * shapes i and j are in active collision.  Either pointer may be NULL. */
 int k2d_read_contacts(k2d_batch* batch, uint8_t* pair_count_dev, uint32_t* shape_adj_dev, void* stream);
 
+/* Reward and termination of the environment built on the engine (Sec. 3.2, "Reward"): the episode of an
+ * environment ends with reward +1 if an active green shape is in active collision (a manifold point with
+ * penetration > 0 at the last substep) with an active blue shape, else with reward -1 if it is with a red
+ * shape; to this the dense term kappa * (d_t - d_{t+1}) is added, d = smallest centre distance over the
+ * active (green, blue) pairs.  A shape's role is the integer in bits 8.. of its shape_flags.
+ * dist_dev: float [n_envs], in: d_t (negative = no previous step, dense term 0), out: d_{t+1} (0 if the
+ * environment has no green or no blue shape; the dense term is then 0 too);
+ * reward_dev: float [n_envs]; done_dev: uint8 [n_envs] (1 = episode ended).  Device memory, caller-owned. */
+typedef struct {
+  float kappa;                               /* weight of the dense term */
+  int32_t role_green, role_blue, role_red;   /* which role integers mean green, blue, red */
+} k2d_reward_params;
+int k2d_read_outcome(k2d_batch* batch, const k2d_reward_params* params, float* dist_dev, float* reward_dev,
+                     uint8_t* done_dev, void* stream);
+
 /* Copies full records ([n_envs][state_words] words, layout above) out of / into the batch
  * (checkpoint and resume; k2d_write_state keeps the accumulators it is given). */
 int k2d_read_state(k2d_batch* batch, void* records_dev, void* stream);

@@ -37,6 +37,11 @@ _LAYOUT_FIELDS = ["n_shapes", "n_pairs", "pos_x", "pos_y", "theta", "vel_x", "ve
                   "state_words", "obs_dim"]
 
 
+class k2d_reward_params(ctypes.Structure):
+    _fields_ = [("kappa", ctypes.c_float), ("role_green", ctypes.c_int32), ("role_blue", ctypes.c_int32),
+                ("role_red", ctypes.c_int32)]
+
+
 class k2d_layout(ctypes.Structure):
     _fields_ = [(n if n != "lambda" else "lambda_", ctypes.c_int32) for n in _LAYOUT_FIELDS]
 
@@ -62,6 +67,7 @@ def lib():
         L.k2d_step_reset.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp]
         L.k2d_read_obs.argtypes = [vp, vp, vp]
         L.k2d_read_contacts.argtypes = [vp, vp, vp, vp]
+        L.k2d_read_outcome.argtypes = [vp, ctypes.POINTER(k2d_reward_params), vp, vp, vp, vp]
         L.k2d_read_state.argtypes = [vp, vp, vp]
         L.k2d_write_state.argtypes = [vp, vp, vp]
         _lib = L
@@ -69,7 +75,7 @@ def lib():
 
 
 EXPORTS = ["k2d_get_layout", "k2d_state_bytes", "k2d_alloc_batch", "k2d_free_batch", "k2d_reset", "k2d_step",
-           "k2d_step_reset",
+           "k2d_step_reset", "k2d_read_outcome",
            "k2d_read_obs", "k2d_read_contacts", "k2d_read_state", "k2d_write_state"]
 
 
@@ -258,6 +264,18 @@ class Batch:
         obs = self.torch.empty((self.n_envs, self.layout["obs_dim"]), dtype=self.torch.float32, device=self.device)
         _check(lib().k2d_read_obs(self._h, obs.data_ptr(), self._stream()), "k2d_read_obs")
         return obs
+
+    def read_outcome(self, dist, kappa=1.0, green=1, blue=2, red=3):
+        """Reward and termination (Sec. 3.2).  dist: device float32 [n_envs], d_t in, d_{t+1} out (negative =
+        first step of an episode).  Returns (reward float32 [n_envs], done uint8 [n_envs])."""
+        torch = self.torch
+        assert dist.is_cuda and dist.dtype == torch.float32 and dist.numel() == self.n_envs and dist.is_contiguous()
+        reward = torch.empty(self.n_envs, dtype=torch.float32, device=self.device)
+        done = torch.empty(self.n_envs, dtype=torch.uint8, device=self.device)
+        rp = k2d_reward_params(float(kappa), int(green), int(blue), int(red))
+        _check(lib().k2d_read_outcome(self._h, ctypes.byref(rp), dist.data_ptr(), reward.data_ptr(), done.data_ptr(),
+                                      self._stream()), "k2d_read_outcome")
+        return reward, done
 
     def read_contacts(self):
         torch = self.torch

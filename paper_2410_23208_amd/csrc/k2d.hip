@@ -1357,6 +1357,57 @@ __global__ void k2d_contacts_kernel(const float* state, uint8_t* pair_count, uin
     }
 }
 
+// Reward and termination (Sec. 3.2): 16 lanes per environment, lane i looks at shape i.  A green shape in
+// active collision with a blue one ends the episode with +1, with a red one with -1; the dense term is
+// kappa * (d_t - d_{t+1}), d = smallest centre distance over the active (green, blue) pairs.
+__global__ void __launch_bounds__(64) k2d_outcome_kernel(const float* state, float* dist, float* reward,
+                                                         uint8_t* done, int n_envs, int rec_words, k2d_layout L,
+                                                         float kappa, int green, int blue, int red) {
+  const int lane = threadIdx.x, i = lane & 15;
+  const int env = blockIdx.x * 4 + (lane >> 4);
+  const bool ok = env < n_envs;
+  const float* S = state + (size_t)(ok ? env : 0) * rec_words;
+  const unsigned char* ps = reinterpret_cast<const unsigned char*>(S + L.pair_state);
+  const int N = L.n_shapes;
+  const bool mine = ok && i < N;
+  const int fl = mine ? __float_as_int(S[L.shape_flags + i]) : 0;
+  const bool act = fl & 1;
+  const int role = act ? (fl >> 8) : -1;
+  const float px = mine ? S[L.pos_x + i] : 0.f, py = mine ? S[L.pos_y + i] : 0.f;
+  bool goal = false, bad = false;
+  float best = INFINITY;
+  for (int j = 0; j < N; ++j) {   // (every lane takes part in the exchange; only green lanes use it)
+    const int rj = __shfl(role, j, 16);
+    const float qx = __shfl(px, j, 16), qy = __shfl(py, j, 16);
+    if (role == green && j != i && rj >= 0) {
+      const int a = min(i, j), b = max(i, j);
+      const bool touching = (ps[a * (2 * N - a - 1) / 2 + (b - a - 1)] & 3) != 0;
+      if (rj == blue) {
+        goal |= touching;
+        const float dx = qx - px, dy = qy - py;
+        best = fminf(best, sqrtf(dx * dx + dy * dy));
+      } else if (rj == red) {
+        bad |= touching;
+      }
+    }
+  }
+  for (int d = 8; d >= 1; d >>= 1) {
+    best = fminf(best, __shfl_xor(best, d, 16));
+    goal |= (bool)__shfl_xor((int)goal, d, 16);
+    bad |= (bool)__shfl_xor((int)bad, d, 16);
+  }
+  if (ok && i == 0) {
+    const bool have = best < INFINITY;
+    const float d_new = have ? best : 0.f;
+    const float d_prev = dist[env];
+    const float dense = (d_prev >= 0.f && have) ? kappa * (d_prev - d_new) : 0.f;
+    const float sparse = goal ? 1.f : (bad ? -1.f : 0.f);
+    reward[env] = sparse + dense;
+    done[env] = (goal || bad) ? 1 : 0;
+    dist[env] = d_new;
+  }
+}
+
 // ---------------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------------
@@ -1510,6 +1561,16 @@ int k2d_read_contacts(k2d_batch* b, uint8_t* pair_count_dev, uint32_t* shape_adj
   if (!pair_count_dev && !shape_adj_dev) return K2D_OK;
   hipLaunchKernelGGL(k2d_contacts_kernel, dim3(b->n_envs), dim3(128), 0, static_cast<hipStream_t>(stream), b->state,
                      pair_count_dev, shape_adj_dev, b->n_envs, b->rec_words, b->layout);
+  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+}
+
+int k2d_read_outcome(k2d_batch* b, const k2d_reward_params* rp, float* dist_dev, float* reward_dev, uint8_t* done_dev,
+                     void* stream) {
+  if (!b || !rp || !dist_dev || !reward_dev || !done_dev) return K2D_E_ARG;
+  if (b->layout.n_shapes > 16) return K2D_E_CAP;
+  hipLaunchKernelGGL(k2d_outcome_kernel, dim3((b->n_envs + 3) / 4), dim3(64), 0, static_cast<hipStream_t>(stream),
+                     b->state, dist_dev, reward_dev, done_dev, b->n_envs, b->rec_words, b->layout, rp->kappa,
+                     rp->role_green, rp->role_blue, rp->role_red);
   return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
 }
 

@@ -168,6 +168,39 @@ def test_resets_inside_one_launch(cfg, n, steps):
         assert np.array_equal(gs[k], os_[k]), k
 
 
+@pytest.mark.parametrize("cfg,n,steps", [(3, 131, 12), (2, 259, 40), (0, 67, 30)])
+def test_reward_and_termination(cfg, n, steps):
+    """k2d_read_outcome after every step against the outcome oracle (Sec. 3.2): flags and floats bit for bit."""
+    import torch
+    import paper_2410_23208_amd as k2d
+    from oracle.k2d_oracle import Oracle
+    from oracle import k2d_env
+    caps, prm, sc = scenegen.make_scene(cfg, n_envs=n)
+    N = caps[0] + caps[1]
+    act = scenegen.make_actions(cfg, steps, n)
+    o = Oracle(caps, n, prm, "f32")
+    o.load_scene(sc)
+    b = k2d.Batch(caps, n, prm)
+    b.reset(k2d.pack_scenes(caps, sc))
+    act_d = torch.from_numpy(act).cuda()
+    d_ref = np.full(n, -1.0, dtype=np.float32)
+    d_gpu = torch.full((n,), -1.0, dtype=torch.float32, device="cuda")
+    n_done = n_dense = 0
+    for s in range(steps):
+        o.step(act[s:s + 1])
+        b.step(act_d[s:s + 1].contiguous())
+        st = o.state()
+        r_ref, done_ref, d_ref = k2d_env.outcome(st["pos"].reshape(n, N, 2), sc["role"], sc["active"], st["pair_count"],
+                                                 d_ref, 0.25)
+        r, done = b.read_outcome(d_gpu, kappa=0.25)
+        assert np.array_equal(done.cpu().numpy(), done_ref), s
+        assert np.array_equal(r.cpu().numpy(), r_ref), s
+        assert np.array_equal(d_gpu.cpu().numpy(), d_ref), s
+        n_done += int(done_ref.sum())
+        n_dense += int(((r_ref != 0) & (done_ref == 0)).sum())
+    assert n_done > 0 and n_dense > n
+
+
 # ------------------------------------------------------------------------------------------ edge cases
 def _hand_scene_parity(sb, prm, steps, n_envs=1):
     sc = sb.scene()
