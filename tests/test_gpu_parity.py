@@ -50,6 +50,20 @@ def test_bit_identical_rollouts(cfg, steps):
     assert (os_["pair_count"] > 0).sum() > 0
 
 
+@pytest.mark.parametrize("cfg,episode,n,steps", [(3, 1, 259, 40), (3, 2, 131, 80), (2, 3, 387, 48), (1, 4, 259, 64),
+                                                 (4, 5, 259, 48), (0, 6, 131, 120)])
+def test_bit_identical_other_episodes(cfg, episode, n, steps):
+    """Other draws of the same workloads (the generator's episode counter), other batch sizes."""
+    caps, prm, sc = scenegen.make_scene(cfg, n_envs=n, episode=episode)
+    act = scenegen.make_actions(cfg, steps, n)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b = parity.run_gpu(caps, prm, sc, act)
+    gs, os_ = b.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    assert (os_["pair_count"] > 0).sum() > n
+
+
 def test_contacts_and_observation_outputs():
     b, o, caps = _both(3, 131, 40)
     pc, adj = b.read_contacts()
