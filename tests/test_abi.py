@@ -62,6 +62,13 @@ def test_argument_errors_without_device_work():
     assert lib.k2d_reset(h, None, None, 4, None) == -1
     assert lib.k2d_reset(h, fake, None, 9, None) == -3
     assert lib.k2d_read_obs(h, None, None) == -1
+    assert lib.k2d_step_reset(h, fake, 4, 1, None, 3, fake, None) == -1           # no level pool
+    assert lib.k2d_step_reset(h, fake, 4, 1, fake, 0, fake, None) == -1           # empty level pool
+    assert lib.k2d_step_reset(h, fake, 4, 1, fake, 3, None, None) == -1           # no schedule
+    assert lib.k2d_step_reset(h, fake, 5, 1, fake, 3, fake, None) == -3
+    rp = binding.k2d_reward_params(1.0, 1, 2, 3)
+    assert lib.k2d_read_outcome(h, None, fake, fake, fake, None) == -1
+    assert lib.k2d_read_outcome(h, ctypes.byref(rp), None, fake, fake, None) == -1
     assert lib.k2d_free_batch(h) == 0
 
 
