@@ -97,7 +97,8 @@ typedef struct k2d_batch k2d_batch; /* opaque host descriptor */
 /* Fills `out` for the given capacities.  K2D_E_CAP if unsupported. */
 int k2d_get_layout(const k2d_caps* caps, k2d_layout* out);
 
-/* Bytes of device memory the caller must provide for `n_envs` environments (0 on bad arguments). */
+/* Bytes of device memory the caller must provide for `n_envs` environments (0 on bad arguments): the records
+ * and, behind them, eight bytes per environment in which a launch sorts the environments by expected work. */
 size_t k2d_state_bytes(const k2d_caps* caps, int n_envs);
 
 /* Binds a caller-owned device buffer (>= k2d_state_bytes, 256-byte aligned) as the state of a new batch.

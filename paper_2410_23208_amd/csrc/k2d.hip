@@ -578,7 +578,8 @@ template <class K, bool RESET>
 __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ state, const float* __restrict__ actions,
                                                       int n_envs, int n_steps, Params prm,
                                                       const float* __restrict__ levels, int n_level_records,
-                                                      const int32_t* __restrict__ reset_level) {
+                                                      const int32_t* __restrict__ reset_level,
+                                                      const int32_t* __restrict__ order) {
   using S = Step<K>;
   constexpr k2d_layout L = K::L;
   constexpr int N = K::N, P = K::P, J = K::J, T = K::T, G = K::G, R = K::R, GP = K::GP, H = K::H;
@@ -587,17 +588,21 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
   const int lane = threadIdx.x;
   const int g = lane / G, k = lane % G;
   const int kp = k % GP, rpar = k / GP;   // this lane's pair slot within a round, and which rounds it takes
-  const int env0 = blockIdx.x * K::EPW;
-  const int env = env0 + g;
-  const bool env_ok = env < n_envs;
+  // which environments this wavefront steps: a launch may come with an ordering of the environments
+  // (slot -> environment, -1 = none) that puts similar ones together; without one, slot s is environment s
+  const int slot0 = blockIdx.x * K::EPW;
+  auto env_of = [&](int slot) { return order ? order[slot] : (slot < n_envs ? slot : -1); };
+  const int env = env_of(slot0 + g);
+  const bool env_ok = env >= 0;
   float* E = lds + g * K::LDS_STRIDE;
   float* Rg = state + (size_t)(env_ok ? env : 0) * K::REC_WORDS;   // this environment's HBM record
 
   // ---- load the scene description into LDS, one environment after the other, 64 words at a time ----
   for (int e = 0; e < K::EPW; ++e) {
     float* dst = lds + e * K::LDS_STRIDE;
-    if (env0 + e < n_envs) {
-      const float* src = state + (size_t)(env0 + e) * K::REC_WORDS;
+    const int env_e = env_of(slot0 + e);
+    if (env_e >= 0) {
+      const float* src = state + (size_t)env_e * K::REC_WORDS;
       for (int w = lane; w < L.scene_words; w += 64) dst[w] = src[w];
     } else {
       for (int w = lane; w < L.scene_words; w += 64) dst[w] = 0.f;   // all-inactive padding environment
@@ -1221,9 +1226,10 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
 
   // ---- write back: dynamic shape state, joint accumulators, pair states ----
   for (int e = 0; e < K::EPW; ++e) {
-    if (env0 + e < n_envs) {
+    const int env_e = env_of(slot0 + e);
+    if (env_e >= 0) {
       const float* src = lds + e * K::LDS_STRIDE;
-      float* dst = state + (size_t)(env0 + e) * K::REC_WORDS;
+      float* dst = state + (size_t)env_e * K::REC_WORDS;
       for (int w = lane; w < 6 * N; w += 64) dst[w] = src[w];
       for (int w = lane; w < 3 * J; w += 64) dst[L.acc_x + w] = src[L.acc_x + w];
     }
@@ -1357,6 +1363,51 @@ __global__ void k2d_contacts_kernel(const float* state, uint8_t* pair_count, uin
     }
 }
 
+// Ordering of the environments for one launch of the step kernel (slot -> environment).  Environments are
+// sorted by how much work they are expected to be (active pairs of the last substep, then movable shapes),
+// so that a wavefront steps four similar ones instead of waiting for the busiest of a random four; and when
+// all wavefronts are resident at once, block b and block b + blocks_per_round share a SIMD, so the busiest
+// wavefronts are paired with the idlest.  The result of the step does not depend on the ordering.
+// Two kernels: the keys (one lane per environment), then a counting sort over 256 key values in one workgroup.
+__global__ void k2d_order_keys_kernel(const float* state, int32_t* keys, int n_envs, int rec_words, k2d_layout L) {
+  const int env = blockIdx.x * blockDim.x + threadIdx.x;
+  if (env >= n_envs) return;
+  const float* S = state + (size_t)env * rec_words;
+  const unsigned* ps = reinterpret_cast<const unsigned*>(S + L.pair_state);
+  int pairs = 0, movable = 0;
+  for (int w = 0; w < (L.n_pairs + 3) / 4; ++w) {   // four pair-state bytes per word (the padding bytes are zero)
+    const unsigned v = ps[w] & 0x03030303u;
+    pairs += ((v & 0xffu) != 0) + ((v & 0xff00u) != 0) + ((v & 0xff0000u) != 0) + ((v & 0xff000000u) != 0);
+  }
+  for (int i = 0; i < L.n_shapes; ++i)
+    movable += (__float_as_int(S[L.shape_flags + i]) & 1) && (S[L.inv_mass + i] > 0.f);
+  keys[env] = 255 - min(255, 8 * pairs + movable);   // busiest first
+}
+__global__ void __launch_bounds__(1024) k2d_order_kernel(const int32_t* keys, int32_t* order, int n_envs, int n_slots,
+                                                         int epw, int blocks_per_round) {
+  __shared__ int count[256], start[256];
+  const int t = threadIdx.x;
+  if (t < 256) count[t] = 0;
+  __syncthreads();
+  for (int env = t; env < n_envs; env += blockDim.x) atomicAdd(&count[keys[env]], 1);
+  __syncthreads();
+  if (t == 0) {
+    int acc = 0;
+    for (int k = 0; k < 256; ++k) { start[k] = acc; acc += count[k]; }
+  }
+  for (int sl = t; sl < n_slots; sl += blockDim.x) order[sl] = -1;
+  __syncthreads();
+  const int n_blocks = n_slots / epw;
+  for (int env = t; env < n_envs; env += blockDim.x) {
+    const int rank = atomicAdd(&start[keys[env]], 1);
+    int wr = rank / epw;   // rank of the wavefront, busiest first
+    int block = wr;
+    if (n_blocks <= 2 * blocks_per_round && wr >= blocks_per_round)   // one round: idlest next to busiest
+      block = n_blocks - 1 - (wr - blocks_per_round);
+    order[block * epw + rank % epw] = env;
+  }
+}
+
 // Reward and termination (Sec. 3.2): 16 lanes per environment, lane i looks at shape i.  A green shape in
 // active collision with a blue one ends the episode with +1, with a red one with -1; the dense term is
 // kappa * (d_t - d_{t+1}), d = smallest centre distance over the active (green, blue) pairs.
@@ -1431,7 +1482,8 @@ int rec_words_of(int cls) { return cls == 0 ? CfgS::REC_WORDS : cls == 1 ? CfgM:
 
 template <class K, bool RESET>
 int launch_step(float* state, const float* actions, int n_envs, int n_steps, const Params& prm, const float* levels,
-                int n_levels, const int32_t* reset_level, hipStream_t st) {
+                int n_levels, const int32_t* reset_level, int32_t* order, int rec_words, const k2d_layout& layout,
+                hipStream_t st) {
   static bool attr_done = false;
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k2d_step_kernel<K, RESET>),
@@ -1440,8 +1492,16 @@ int launch_step(float* state, const float* actions, int n_envs, int n_steps, con
     attr_done = true;
   }
   int grid = (n_envs + K::EPW - 1) / K::EPW;
+  if (order) {   // (a launch of a few steps is not worth the ordering pass)
+    constexpr int kBlocksPerRound = 1024;   // 256 CUs x 4 SIMDs: blocks b and b + 1024 of a resident launch share a SIMD
+    int32_t* keys = order + grid * K::EPW;
+    hipLaunchKernelGGL(k2d_order_keys_kernel, dim3((n_envs + 255) / 256), dim3(256), 0, st, state, keys, n_envs, rec_words,
+                       layout);
+    hipLaunchKernelGGL(k2d_order_kernel, dim3(1), dim3(1024), 0, st, keys, order, n_envs, grid * K::EPW, K::EPW,
+                       kBlocksPerRound);
+  }
   hipLaunchKernelGGL((k2d_step_kernel<K, RESET>), dim3(grid), dim3(64), K::LDS_BYTES, st, state, actions, n_envs,
-                     n_steps, prm, levels, n_levels, reset_level);
+                     n_steps, prm, levels, n_levels, reset_level, order);
   return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
 }
 
@@ -1455,7 +1515,40 @@ struct k2d_batch {
   int n_envs;
   int rec_words;
   float* state;
+  int32_t* order;   // behind the records in the caller's buffer: slot -> environment for one launch
 };
+
+// launches of fewer steps than this keep the identity ordering (the ordering pass would cost more than it saves)
+constexpr int kOrderMinSteps = 8;
+static size_t records_bytes(int cls, int n_envs) {
+  return ((size_t)n_envs * rec_words_of(cls) * sizeof(float) + 255) / 256 * 256;
+}
+
+static Params device_params(const k2d_params& p) {
+  Params prm;
+  prm.h = p.dt / (float)p.n_substeps;
+  prm.gravity_y = p.gravity_y;
+  prm.n_substeps = p.n_substeps;
+  prm.n_iters = p.n_iters;
+  prm.warm_start = p.warm_start;
+  prm.alpha = p.alpha; prm.beta = p.beta; prm.gamma = p.gamma; prm.rho = p.rho; prm.slop = p.slop;
+  prm.rest_thr = p.restitution_threshold;
+  prm.clip_thr = p.clip_thruster_01;
+  prm.joint_alpha = p.joint_alpha; prm.joint_beta = p.joint_beta; prm.tie_eps = p.tie_eps;
+  return prm;
+}
+
+template <bool RESET>
+static int step_launch(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, const float* lv, int n_levels,
+                       const int32_t* reset_level_dev, hipStream_t st) {
+  const Params prm = device_params(b->params);
+  int32_t* ord = n_steps >= kOrderMinSteps ? b->order : nullptr;
+  switch (b->cls) {
+    case 0: return launch_step<CfgS, RESET>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
+    case 1: return launch_step<CfgM, RESET>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
+    default: return launch_step<CfgL, RESET>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
+  }
+}
 
 extern "C" {
 
@@ -1469,7 +1562,7 @@ int k2d_get_layout(const k2d_caps* caps, k2d_layout* out) {
 size_t k2d_state_bytes(const k2d_caps* caps, int n_envs) {
   int cls = caps_class(caps);
   if (cls < 0 || n_envs < 1) return 0;
-  return (size_t)n_envs * rec_words_of(cls) * sizeof(float);
+  return records_bytes(cls, n_envs) + 2 * (size_t)((n_envs + 3) / 4 * 4) * sizeof(int32_t);   // + ordering, keys
 }
 
 int k2d_alloc_batch(const k2d_caps* caps, const k2d_params* params, int n_envs, void* state_dev, size_t state_bytes,
@@ -1489,6 +1582,7 @@ int k2d_alloc_batch(const k2d_caps* caps, const k2d_params* params, int n_envs, 
   b->n_envs = n_envs;
   b->rec_words = rec_words_of(cls);
   b->state = static_cast<float*>(state_dev);
+  b->order = reinterpret_cast<int32_t*>(static_cast<char*>(state_dev) + records_bytes(cls, n_envs));
   *out = b;
   return K2D_OK;
 }
@@ -1506,44 +1600,18 @@ int k2d_reset(k2d_batch* b, const void* scenes_dev, const int32_t* env_ids_dev, 
   return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
 }
 
-static Params device_params(const k2d_params& p) {
-  Params prm;
-  prm.h = p.dt / (float)p.n_substeps;
-  prm.gravity_y = p.gravity_y;
-  prm.n_substeps = p.n_substeps;
-  prm.n_iters = p.n_iters;
-  prm.warm_start = p.warm_start;
-  prm.alpha = p.alpha; prm.beta = p.beta; prm.gamma = p.gamma; prm.rho = p.rho; prm.slop = p.slop;
-  prm.rest_thr = p.restitution_threshold;
-  prm.clip_thr = p.clip_thruster_01;
-  prm.joint_alpha = p.joint_alpha; prm.joint_beta = p.joint_beta; prm.tie_eps = p.tie_eps;
-  return prm;
-}
-
 int k2d_step(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, void* stream) {
   if (!b || !actions_dev || n_steps < 1) return K2D_E_ARG;
   if (n_envs != b->n_envs) return K2D_E_SIZE;
-  const Params prm = device_params(b->params);
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  switch (b->cls) {
-    case 0: return launch_step<CfgS, false>(b->state, actions_dev, n_envs, n_steps, prm, nullptr, 0, nullptr, st);
-    case 1: return launch_step<CfgM, false>(b->state, actions_dev, n_envs, n_steps, prm, nullptr, 0, nullptr, st);
-    default: return launch_step<CfgL, false>(b->state, actions_dev, n_envs, n_steps, prm, nullptr, 0, nullptr, st);
-  }
+  return step_launch<false>(b, actions_dev, n_envs, n_steps, nullptr, 0, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int k2d_step_reset(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, const void* levels_dev,
                    int n_levels, const int32_t* reset_level_dev, void* stream) {
   if (!b || !actions_dev || n_steps < 1 || !levels_dev || n_levels < 1 || !reset_level_dev) return K2D_E_ARG;
   if (n_envs != b->n_envs) return K2D_E_SIZE;
-  const Params prm = device_params(b->params);
-  const float* lv = static_cast<const float*>(levels_dev);
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  switch (b->cls) {
-    case 0: return launch_step<CfgS, true>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, st);
-    case 1: return launch_step<CfgM, true>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, st);
-    default: return launch_step<CfgL, true>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, st);
-  }
+  return step_launch<true>(b, actions_dev, n_envs, n_steps, static_cast<const float*>(levels_dev), n_levels,
+                           reset_level_dev, static_cast<hipStream_t>(stream));
 }
 
 int k2d_read_obs(k2d_batch* b, float* obs_dev, void* stream) {

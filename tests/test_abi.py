@@ -36,7 +36,7 @@ def test_layout_matches_header_and_table4():
         assert L["lambda"] % 4 == 0 and L["state_words"] == L["pair_state"] + (n_pairs + 3) // 4
         assert L["obs_dim"] == 23 * P + 15 * C + 11 * J + 6 * T
         assert k2d.state_bytes(caps, 10) >= 10 * 4 * L["state_words"]
-        assert k2d.state_bytes(caps, 10) == 10 * k2d.state_bytes(caps, 1)
+        assert k2d.state_bytes(caps, 1000) < 1000 * k2d.state_bytes(caps, 1)      # records + a small per-environment tail
 
 
 def test_argument_errors_without_device_work():
