@@ -1365,9 +1365,8 @@ __global__ void k2d_contacts_kernel(const float* state, uint8_t* pair_count, uin
 
 // Ordering of the environments for one launch of the step kernel (slot -> environment).  Environments are
 // sorted by how much work they are expected to be (active pairs of the last substep, then movable shapes),
-// so that a wavefront steps four similar ones instead of waiting for the busiest of a random four; and when
-// all wavefronts are resident at once, block b and block b + blocks_per_round share a SIMD, so the busiest
-// wavefronts are paired with the idlest.  The result of the step does not depend on the ordering.
+// busiest first, so that a wavefront steps four similar ones instead of waiting for the busiest of a random
+// four.  The result of the step does not depend on the ordering.
 // Two kernels: the keys (one lane per environment), then a counting sort over 256 key values in one workgroup.
 __global__ void k2d_order_keys_kernel(const float* state, int32_t* keys, int n_envs, int rec_words, k2d_layout L) {
   const int env = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1383,8 +1382,7 @@ __global__ void k2d_order_keys_kernel(const float* state, int32_t* keys, int n_e
     movable += (__float_as_int(S[L.shape_flags + i]) & 1) && (S[L.inv_mass + i] > 0.f);
   keys[env] = 255 - min(255, 8 * pairs + movable);   // busiest first
 }
-__global__ void __launch_bounds__(1024) k2d_order_kernel(const int32_t* keys, int32_t* order, int n_envs, int n_slots,
-                                                         int epw, int blocks_per_round) {
+__global__ void __launch_bounds__(1024) k2d_order_kernel(const int32_t* keys, int32_t* order, int n_envs, int n_slots) {
   __shared__ int count[256], start[256];
   const int t = threadIdx.x;
   if (t < 256) count[t] = 0;
@@ -1397,15 +1395,7 @@ __global__ void __launch_bounds__(1024) k2d_order_kernel(const int32_t* keys, in
   }
   for (int sl = t; sl < n_slots; sl += blockDim.x) order[sl] = -1;
   __syncthreads();
-  const int n_blocks = n_slots / epw;
-  for (int env = t; env < n_envs; env += blockDim.x) {
-    const int rank = atomicAdd(&start[keys[env]], 1);
-    int wr = rank / epw;   // rank of the wavefront, busiest first
-    int block = wr;
-    if (n_blocks <= 2 * blocks_per_round && wr >= blocks_per_round)   // one round: idlest next to busiest
-      block = n_blocks - 1 - (wr - blocks_per_round);
-    order[block * epw + rank % epw] = env;
-  }
+  for (int env = t; env < n_envs; env += blockDim.x) order[atomicAdd(&start[keys[env]], 1)] = env;
 }
 
 // Reward and termination (Sec. 3.2): 16 lanes per environment, lane i looks at shape i.  A green shape in
@@ -1493,12 +1483,10 @@ int launch_step(float* state, const float* actions, int n_envs, int n_steps, con
   }
   int grid = (n_envs + K::EPW - 1) / K::EPW;
   if (order) {   // (a launch of a few steps is not worth the ordering pass)
-    constexpr int kBlocksPerRound = 1024;   // 256 CUs x 4 SIMDs: blocks b and b + 1024 of a resident launch share a SIMD
     int32_t* keys = order + grid * K::EPW;
     hipLaunchKernelGGL(k2d_order_keys_kernel, dim3((n_envs + 255) / 256), dim3(256), 0, st, state, keys, n_envs, rec_words,
                        layout);
-    hipLaunchKernelGGL(k2d_order_kernel, dim3(1), dim3(1024), 0, st, keys, order, n_envs, grid * K::EPW, K::EPW,
-                       kBlocksPerRound);
+    hipLaunchKernelGGL(k2d_order_kernel, dim3(1), dim3(1024), 0, st, keys, order, n_envs, grid * K::EPW);
   }
   hipLaunchKernelGGL((k2d_step_kernel<K, RESET>), dim3(grid), dim3(64), K::LDS_BYTES, st, state, actions, n_envs,
                      n_steps, prm, levels, n_levels, reset_level, order);
