@@ -128,13 +128,13 @@ struct Cfg {
   static constexpr int X_WV = align_up(X_BRAD + N, 2);     // world vertices, float2 [4][P]
   static constexpr int X_WN = X_WV + 8 * P;                // outward unit edge normals, float2 [4][P]
   static constexpr int NID = R * GP;                       // pair ids: id = r * GP + k (canonical order)
-  static constexpr int X_TABLE = align_up(X_WN + 8 * P, 4);        // bytes [NID]: pool index of pair id, 0xFF = none
+  static constexpr int X_TABLE = align_up(X_WN + 8 * P, 4);        // bytes [NID]: number of the active pair with this id (set for the pairs not held in registers)
   static constexpr int TABLE_W = align_up((NID + 3) / 4, 4);       // read back four words at a time
   static constexpr int X_LIST = X_TABLE + TABLE_W;         // bytes [NID]: candidate ids, one shape-type mix after the other
   static constexpr int X_JOINED = X_LIST;                  // (launch set-up only) bit j of word i: shapes i, j joined
   static constexpr int LIST_W = (NID + 3) / 4 > N ? (NID + 3) / 4 : N;
   static constexpr int LCAP = 16;                          // a level holds at most one pair per movable shape
-  static constexpr int X_SCHED = X_LIST + LIST_W;          // bytes [R][LCAP]: pool indices, level by level
+  static constexpr int X_SCHED = X_LIST + LIST_W;          // bytes [R][LCAP]: numbers of the active pairs not held in registers, level by level
   static constexpr int X_PSTATE = align_up(X_SCHED + R * LCAP / 4, 4);   // bytes [G][16]: active-point bits of pair (r, k) at [k][r]
   static constexpr int X_BITMAP = X_PSTATE + GP * 4;       // 4 words: bit id set = pair id is active and not held in registers
   static constexpr int X_RMASK = X_BITMAP + 4;             // [G] words: bit r set = the shape has an active pair in round r
@@ -640,7 +640,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     E[K::X_JOINED + i] = i2f(0);
   }
   wave_sync();
-  // joints: lane j of the group owns joint j for the whole launch
+  // joints: lane j of the group owns joint j for the whole episode
   bool j_live = false, j_fixed = false, j_motor = false, j_limited = false;
   int ja = 0, jb = 0;
   float j_aax = 0.f, j_aay = 0.f, j_abx = 0.f, j_aby = 0.f, j_thf = 0.f, j_speed = 0.f, j_power = 0.f;
@@ -714,7 +714,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     k2d_sincos(E[L.thr_angle + k], t_dy, t_dx);
     t_power = E[L.thr_power + k];
   }
-  // pairs: lane k tests pair k of every round; eligibility is fixed for the launch
+  // pairs: the lane tests pair k % GP of the rounds r with r % H == k / GP; eligibility is fixed for the episode
   unsigned char* table = reinterpret_cast<unsigned char*>(E + K::X_TABLE);
   unsigned char* cand_list = reinterpret_cast<unsigned char*>(E + K::X_LIST);
   unsigned char* sched = reinterpret_cast<unsigned char*>(E + K::X_SCHED);
