@@ -144,6 +144,31 @@ int k2d_read_obs(k2d_batch* batch, float* obs_dev, void* stream);
  * shapes i and j are in active collision.  Either pointer may be NULL. */
 int k2d_read_contacts(k2d_batch* batch, uint8_t* pair_count_dev, uint32_t* shape_adj_dev, void* stream);
 
+/* Symbolic-Entity observation (Sec. 3.2 "Observation Space", Sec. 4, Appendix C Tables 5-7): the set of
+ * entities of every environment, and the four attention masks of the entity model.  Device memory, caller-owned.
+ *   shapes_dev    float [n_envs][N][30]: position 2, velocity 2, inverse mass, inverse inertia, density,
+ *                 tanh(angular velocity / 10), one-hot role (roles 0..3), sin and cos of the rotation, friction,
+ *                 restitution, one-hot type (circle, polygon), radius (circles), vertices 8 and one-hot
+ *                 (triangle, rectangle) (polygons), active
+ *   joints_dev    float [n_envs][2J][11]: active, fixed, anchor on `from` 2, anchor on `to` 2, motor power,
+ *                 motor speed, motor on, sin and cos of rotation(from) - rotation(to).  Entity 2q is joint q seen
+ *                 from its shape a, entity 2q+1 the same joint with from and to swapped (Appendix C)
+ *   joint_idx_dev int32 [n_envs][2J][2]: the (from, to) shapes of every joint entity
+ *   thrusters_dev float [n_envs][T][6]: active, position 2 (local), power, sin and cos of the local angle;
+ *   thruster_idx_dev int32 [n_envs][T]: the shape a thruster sits on
+ *   masks_dev     uint32 [n_envs][4][N]: bit j of word i set iff shape i may attend to shape j -- (0) every
+ *                 active shape, (1) itself and the shapes an active joint connects it to, (2) itself and the
+ *                 shapes reachable over any number of joints, (3) the shapes it is in active collision with
+ * joints_dev / joint_idx_dev may be NULL if J = 0, thrusters_dev / thruster_idx_dev if T = 0. */
+int k2d_read_entities(k2d_batch* batch, float* shapes_dev, float* joints_dev, int32_t* joint_idx_dev,
+                      float* thrusters_dev, int32_t* thruster_idx_dev, uint32_t* masks_dev, void* stream);
+
+/* Multi-discrete action space (Sec. 3.2 "Action Space"): every motor is off (0), run forwards (1) or backwards
+ * (2) at full power, every thruster off (0) or on (1).  discrete_dev: int32 [n_rows][J+T] -> actions_dev:
+ * float [n_rows][J+T] (+1, -1, 0), the actions k2d_step consumes; n_rows = n_steps * n_envs. */
+int k2d_decode_actions(const k2d_caps* caps, const int32_t* discrete_dev, float* actions_dev, size_t n_rows,
+                       void* stream);
+
 /* Reward and termination of the environment built on the engine (Sec. 3.2, "Reward"): the episode of an
  * environment ends with reward +1 if an active green shape is in active collision (a manifold point with
  * penetration > 0 at the last substep) with an active blue shape, else with reward -1 if it is with a red

@@ -58,3 +58,104 @@ def outcome(pos, role, active, pair_count, d_prev, kappa, green=1, blue=2, red=3
         reward[e] = f(sparse + dense)
         done[e] = 1 if (goal or bad) else 0
     return reward, done, d_new
+
+
+# ----------------------------------------------------------------------------------------------------------
+# Symbolic-Entity observation (Sec. 3.2 "Observation Space", Sec. 4, Appendix C Tables 5-7) and the
+# multi-discrete action space (Sec. 3.2 "Action Space").
+# ----------------------------------------------------------------------------------------------------------
+N_ROLES = 4
+SHAPE_DIM, JOINT_DIM, THRUSTER_DIM = 30, 11, 6
+
+
+def decode_actions(discrete, J, T):
+    """Multi-discrete actions: a motor is off (0), run forwards (1) or backwards (2) at full power; a
+    thruster is off (0) or on (1).  discrete int [..., J+T] -> float32 [..., J+T]."""
+    d = np.asarray(discrete)
+    out = np.zeros(d.shape, dtype=np.float32)
+    m = d[..., :J]
+    out[..., :J] = np.where(m == 1, 1.0, np.where(m == 2, -1.0, 0.0))
+    out[..., J:] = np.where(d[..., J:] == 1, 1.0, 0.0)
+    return out
+
+
+def entities(flat_obs, scene, shape_adj, caps):
+    """From the engine oracle's flat observation [n, obs_dim] (Tables 5-7, entity after entity), the scene
+    description and the collision adjacency words [n, N]:
+      shapes    float32 [n, N, 30]: position 2, velocity 2, inverse mass, inverse inertia, density,
+                tanh(angular velocity / 10), one-hot role (4), sin, cos of the rotation, friction, restitution,
+                one-hot type (circle, polygon), radius (circles), vertices 8 and one-hot (triangle, rectangle)
+                (polygons), active                                                       (Table 5 + mask)
+      joints    float32 [n, 2J, 11]: active, fixed, anchor on `from` 2, anchor on `to` 2, motor power, motor
+                speed, motor on, sin, cos of rotation(from) - rotation(to); entity 2q is joint q seen from its
+                shape a, entity 2q+1 the same joint with from and to swapped                  (Table 7)
+      joint_idx int32 [n, 2J, 2]: (from, to) shape of every joint entity
+      thrusters float32 [n, T, 6] (Table 6), thruster_idx int32 [n, T]
+      masks     uint32 [n, 4, N]: bit j of word i set iff shape i may attend to shape j -- all active shapes;
+                shapes joined to it by an active joint; shapes reachable over any number of joints; shapes
+                it is colliding with (Sec. 4).  A shape attends to itself in the first three.
+    """
+    P, C, J, T = caps
+    N = P + C
+    flat = np.asarray(flat_obs, dtype=np.float64)
+    n = flat.shape[0]
+    shapes = np.zeros((n, N, SHAPE_DIM), dtype=np.float32)
+    joints = np.zeros((n, 2 * J, JOINT_DIM), dtype=np.float32)
+    jidx = np.zeros((n, 2 * J, 2), dtype=np.int32)
+    thr = np.zeros((n, T, THRUSTER_DIM), dtype=np.float32)
+    tidx = np.zeros((n, T), dtype=np.int32)
+    masks = np.zeros((n, 4, N), dtype=np.uint32)
+    for e in range(n):
+        o = flat[e]
+        for i in range(N):
+            f = o[i * 23:(i + 1) * 23] if i < P else o[P * 23 + (i - P) * 15:P * 23 + (i - P + 1) * 15]
+            s = shapes[e, i]
+            s[0:8] = f[0:8]
+            role = int(f[22] if i < P else f[14])
+            if 0 <= role < N_ROLES:
+                s[8 + role] = 1.0
+            s[12:16] = f[8:12]                          # sin, cos, friction, restitution
+            s[16 if i >= P else 17] = 1.0               # type: circle, polygon
+            if i < P:
+                s[19:27] = f[12:20]
+                s[27 if int(f[20]) == 3 else 28] = 1.0
+                s[29] = f[21]
+            else:
+                s[18] = f[12]
+                s[29] = f[13]
+        act = np.asarray(scene["active"][e]) > 0
+        full = 0
+        for i in range(N):
+            if act[i]:
+                full |= 1 << i
+        direct = [(1 << i) if act[i] else 0 for i in range(N)]
+        base = P * 23 + C * 15
+        for q in range(J):
+            f = o[base + q * 11:base + (q + 1) * 11]
+            a, b = int(scene["joint_a"][e, q]), int(scene["joint_b"][e, q])
+            a, b = min(max(a, 0), N - 1), min(max(b, 0), N - 1)
+            joints[e, 2 * q] = f
+            g = f.copy()
+            g[2:4], g[4:6] = f[4:6], f[2:4]
+            g[9] = -f[9]                                # sin of the opposite rotation; cos is even
+            joints[e, 2 * q + 1] = g
+            jidx[e, 2 * q] = (a, b)
+            jidx[e, 2 * q + 1] = (b, a)
+            if f[0] != 0 and act[a] and act[b] and a != b:
+                direct[a] |= 1 << b
+                direct[b] |= 1 << a
+        reach = list(direct)
+        for k in range(N):                              # transitive closure
+            for i in range(N):
+                if (reach[i] >> k) & 1:
+                    reach[i] |= reach[k]
+        tb = base + J * 11
+        for t in range(T):
+            thr[e, t] = o[tb + t * 6:tb + (t + 1) * 6]
+            tidx[e, t] = min(max(int(scene["thruster_body"][e, t]), 0), N - 1)
+        for i in range(N):
+            masks[e, 0, i] = full if act[i] else 0
+            masks[e, 1, i] = direct[i]
+            masks[e, 2, i] = reach[i]
+            masks[e, 3, i] = int(shape_adj[e, i])
+    return dict(shapes=shapes, joints=joints, joint_idx=jidx, thrusters=thr, thruster_idx=tidx, masks=masks)

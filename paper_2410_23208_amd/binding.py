@@ -67,6 +67,8 @@ def lib():
         L.k2d_step_reset.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp]
         L.k2d_read_obs.argtypes = [vp, vp, vp]
         L.k2d_read_contacts.argtypes = [vp, vp, vp, vp]
+        L.k2d_read_entities.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+        L.k2d_decode_actions.argtypes = [ctypes.POINTER(k2d_caps), vp, vp, ctypes.c_size_t, vp]
         L.k2d_read_outcome.argtypes = [vp, ctypes.POINTER(k2d_reward_params), vp, vp, vp, vp]
         L.k2d_read_state.argtypes = [vp, vp, vp]
         L.k2d_write_state.argtypes = [vp, vp, vp]
@@ -75,7 +77,7 @@ def lib():
 
 
 EXPORTS = ["k2d_get_layout", "k2d_state_bytes", "k2d_alloc_batch", "k2d_free_batch", "k2d_reset", "k2d_step",
-           "k2d_step_reset", "k2d_read_outcome",
+           "k2d_step_reset", "k2d_read_outcome", "k2d_read_entities", "k2d_decode_actions",
            "k2d_read_obs", "k2d_read_contacts", "k2d_read_state", "k2d_write_state"]
 
 
@@ -264,6 +266,32 @@ class Batch:
         obs = self.torch.empty((self.n_envs, self.layout["obs_dim"]), dtype=self.torch.float32, device=self.device)
         _check(lib().k2d_read_obs(self._h, obs.data_ptr(), self._stream()), "k2d_read_obs")
         return obs
+
+    def read_entities(self):
+        """Symbolic-Entity observation: dict of device tensors (shapes, joints, joint_idx, thrusters,
+        thruster_idx, masks), see k2d_read_entities in include/k2d.h."""
+        torch = self.torch
+        n, N, J, T = self.n_envs, self.layout["n_shapes"], self.J, self.T
+        f = lambda *s: torch.empty(s, dtype=torch.float32, device=self.device)
+        i = lambda *s: torch.empty(s, dtype=torch.int32, device=self.device)
+        out = dict(shapes=f(n, N, 30), joints=f(n, 2 * J, 11), joint_idx=i(n, 2 * J, 2), thrusters=f(n, T, 6),
+                   thruster_idx=i(n, T), masks=i(n, 4, N))
+        ptr = lambda t: t.data_ptr() if t.numel() else None
+        _check(lib().k2d_read_entities(self._h, out["shapes"].data_ptr(), ptr(out["joints"]), ptr(out["joint_idx"]),
+                                       ptr(out["thrusters"]), ptr(out["thruster_idx"]), out["masks"].data_ptr(),
+                                       self._stream()), "k2d_read_entities")
+        return out
+
+    def decode_actions(self, discrete):
+        """Multi-discrete device int32 [..., J+T] -> device float32 actions of the same shape."""
+        torch = self.torch
+        assert discrete.is_cuda and discrete.dtype == torch.int32 and discrete.is_contiguous()
+        assert discrete.shape[-1] == self.J + self.T
+        out = torch.empty(discrete.shape, dtype=torch.float32, device=self.device)
+        c = make_caps(self.caps)
+        _check(lib().k2d_decode_actions(ctypes.byref(c), discrete.data_ptr(), out.data_ptr(),
+                                        discrete.numel() // (self.J + self.T), self._stream()), "k2d_decode_actions")
+        return out
 
     def read_outcome(self, dist, kappa=1.0, green=1, blue=2, red=3):
         """Reward and termination (Sec. 3.2).  dist: device float32 [n_envs], d_t in, d_{t+1} out (negative =

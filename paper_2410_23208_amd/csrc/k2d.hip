@@ -1344,6 +1344,116 @@ __global__ void k2d_obs_kernel(const float* state, float* obs, int n_envs, int r
   }
 }
 
+// Symbolic-Entity observation (Sec. 3.2, Sec. 4, Tables 5-7): one thread per entity.  Entities of an
+// environment: N shapes, then two per joint (the joint seen from either of its shapes), then T thrusters.
+__global__ void k2d_entities_kernel(const float* state, float* shapes, float* joints, int32_t* joint_idx,
+                                    float* thrusters, int32_t* thruster_idx, int n_envs, int rec_words, k2d_layout L,
+                                    int P, int C, int J, int T) {
+  const int N = P + C, n_ent = N + 2 * J + T;
+  long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long)n_envs * n_ent) return;
+  const int env = (int)(gid / n_ent), ent = (int)(gid % n_ent);
+  const float* S = state + (size_t)env * rec_words;
+  if (ent < N) {
+    const int i = ent;
+    float* o = shapes + ((size_t)env * N + i) * 30;
+    const int fl = __float_as_int(S[L.shape_flags + i]);
+    float sn, cs;
+    k2d_sincos(S[L.theta + i], sn, cs);
+    o[0] = S[L.pos_x + i]; o[1] = S[L.pos_y + i]; o[2] = S[L.vel_x + i]; o[3] = S[L.vel_y + i];
+    o[4] = S[L.inv_mass + i]; o[5] = S[L.inv_inertia + i]; o[6] = S[L.density + i];
+    o[7] = k2d_tanh(S[L.omega + i] / 10.f);
+    const int role = fl >> 8;
+    for (int r = 0; r < 4; ++r) o[8 + r] = (role == r) ? 1.f : 0.f;
+    o[12] = sn; o[13] = cs; o[14] = S[L.friction + i]; o[15] = S[L.restitution + i];
+    o[16] = (i >= P) ? 1.f : 0.f; o[17] = (i < P) ? 1.f : 0.f;
+    o[18] = (i >= P) ? S[L.radius + (i - P)] : 0.f;
+    const int nv = (i < P) ? __float_as_int(S[L.n_verts + i]) : 0;
+    for (int v = 0; v < 8; ++v) o[19 + v] = (i < P) ? S[L.verts + v * P + i] : 0.f;
+    o[27] = (i < P && nv == 3) ? 1.f : 0.f;
+    o[28] = (i < P && nv != 3) ? 1.f : 0.f;
+    o[29] = (float)(fl & 1);
+  } else if (ent < N + 2 * J) {
+    const int q = (ent - N) >> 1, swapped = (ent - N) & 1;
+    float* o = joints + ((size_t)env * 2 * J + (ent - N)) * 11;
+    const int fl = __float_as_int(S[L.joint_flags + q]);
+    int a = __float_as_int(S[L.joint_a + q]), b = __float_as_int(S[L.joint_b + q]);
+    a = min(max(a, 0), N - 1); b = min(max(b, 0), N - 1);
+    float sn, cs;
+    k2d_sincos(S[L.theta + a] - S[L.theta + b], sn, cs);
+    const float aax = S[L.anchor_a_x + q], aay = S[L.anchor_a_y + q], abx = S[L.anchor_b_x + q], aby = S[L.anchor_b_y + q];
+    o[0] = (float)(fl & 1); o[1] = (float)((fl >> 1) & 1);
+    o[2] = swapped ? abx : aax; o[3] = swapped ? aby : aay;
+    o[4] = swapped ? aax : abx; o[5] = swapped ? aay : aby;
+    o[6] = S[L.motor_power + q]; o[7] = S[L.motor_speed + q]; o[8] = (float)((fl >> 2) & 1);
+    o[9] = swapped ? -sn : sn; o[10] = cs;
+    int32_t* ix = joint_idx + ((size_t)env * 2 * J + (ent - N)) * 2;
+    ix[0] = swapped ? b : a; ix[1] = swapped ? a : b;
+  } else {
+    const int t = ent - N - 2 * J;
+    float* o = thrusters + ((size_t)env * T + t) * 6;
+    const int fl = __float_as_int(S[L.thr_flags + t]);
+    float sn, cs;
+    k2d_sincos(S[L.thr_angle + t], sn, cs);
+    o[0] = (float)(fl & 1); o[1] = S[L.thr_pos_x + t]; o[2] = S[L.thr_pos_y + t]; o[3] = S[L.thr_power + t];
+    o[4] = sn; o[5] = cs;
+    thruster_idx[(size_t)env * T + t] = min(max(__float_as_int(S[L.thr_body + t]), 0), N - 1);
+  }
+}
+
+// The four attention masks of the entity model (Sec. 4): bit j of word i set iff shape i may attend to
+// shape j.  16 lanes per environment, lane i holds the words of shape i.
+__global__ void __launch_bounds__(64) k2d_masks_kernel(const float* state, uint32_t* masks, int n_envs, int rec_words,
+                                                       k2d_layout L, int J) {
+  const int lane = threadIdx.x, i = lane & 15;
+  const int env = blockIdx.x * 4 + (lane >> 4);
+  const bool ok = env < n_envs;
+  const float* S = state + (size_t)(ok ? env : 0) * rec_words;
+  const unsigned char* ps = reinterpret_cast<const unsigned char*>(S + L.pair_state);
+  const int N = L.n_shapes;
+  const bool act = ok && i < N && (__float_as_int(S[L.shape_flags + i]) & 1);
+  unsigned full = 0u;
+  for (int j = 0; j < N; ++j) full |= (unsigned)__shfl((int)act, j, 16) << j;
+  unsigned direct = act ? (1u << i) : 0u;
+  for (int q = 0; q < J; ++q) {
+    const int fl = __float_as_int(S[L.joint_flags + q]);
+    int a = __float_as_int(S[L.joint_a + q]), b = __float_as_int(S[L.joint_b + q]);
+    a = min(max(a, 0), N - 1); b = min(max(b, 0), N - 1);
+    if ((fl & 1) && a != b && ((full >> a) & 1u) && ((full >> b) & 1u)) {
+      if (i == a) direct |= 1u << b;
+      if (i == b) direct |= 1u << a;
+    }
+  }
+  unsigned reach = direct;
+  for (int k = 0; k < N; ++k) {   // transitive closure
+    const unsigned rk = (unsigned)__shfl((int)reach, k, 16);
+    if ((reach >> k) & 1u) reach |= rk;
+  }
+  unsigned touch = 0u;
+  if (ok && i < N)
+    for (int j = 0; j < N; ++j) {
+      if (j == i) continue;
+      const int a = min(i, j), b = max(i, j);
+      if (ps[a * (2 * N - a - 1) / 2 + (b - a - 1)] & 3) touch |= 1u << j;
+    }
+  if (ok && i < N) {
+    uint32_t* m = masks + (size_t)env * 4 * N;
+    m[i] = act ? full : 0u;
+    m[N + i] = direct;
+    m[2 * N + i] = reach;
+    m[3 * N + i] = touch;
+  }
+}
+
+// Multi-discrete actions (Sec. 3.2): a motor is off (0), forwards (1) or backwards (2) at full power, a
+// thruster off (0) or on (1).
+__global__ void k2d_decode_actions_kernel(const int32_t* discrete, float* actions, size_t n, int J, int A) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n) return;
+  const int c = (int)(idx % A), d = discrete[idx];
+  actions[idx] = (c < J) ? (d == 1 ? 1.f : d == 2 ? -1.f : 0.f) : (d == 1 ? 1.f : 0.f);
+}
+
 // Active manifold points per pair and the shape adjacency words, from the pair-state bytes.
 __global__ void k2d_contacts_kernel(const float* state, uint8_t* pair_count, uint32_t* shape_adj, int n_envs,
                                     int rec_words, k2d_layout L) {
@@ -1620,6 +1730,35 @@ int k2d_read_contacts(k2d_batch* b, uint8_t* pair_count_dev, uint32_t* shape_adj
   if (!pair_count_dev && !shape_adj_dev) return K2D_OK;
   hipLaunchKernelGGL(k2d_contacts_kernel, dim3(b->n_envs), dim3(128), 0, static_cast<hipStream_t>(stream), b->state,
                      pair_count_dev, shape_adj_dev, b->n_envs, b->rec_words, b->layout);
+  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+}
+
+int k2d_read_entities(k2d_batch* b, float* shapes_dev, float* joints_dev, int32_t* joint_idx_dev, float* thrusters_dev,
+                      int32_t* thruster_idx_dev, uint32_t* masks_dev, void* stream) {
+  if (!b || !shapes_dev || !masks_dev) return K2D_E_ARG;
+  const k2d_caps& c = b->caps;
+  if ((c.n_joints > 0 && (!joints_dev || !joint_idx_dev)) || (c.n_thrusters > 0 && (!thrusters_dev || !thruster_idx_dev)))
+    return K2D_E_ARG;
+  if (b->layout.n_shapes > 16) return K2D_E_CAP;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const long n = (long)b->n_envs * (c.n_polygons + c.n_circles + 2 * c.n_joints + c.n_thrusters);
+  hipLaunchKernelGGL(k2d_entities_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, b->state, shapes_dev,
+                     joints_dev, joint_idx_dev, thrusters_dev, thruster_idx_dev, b->n_envs, b->rec_words, b->layout,
+                     c.n_polygons, c.n_circles, c.n_joints, c.n_thrusters);
+  hipLaunchKernelGGL(k2d_masks_kernel, dim3((b->n_envs + 3) / 4), dim3(64), 0, st, b->state, masks_dev, b->n_envs,
+                     b->rec_words, b->layout, c.n_joints);
+  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+}
+
+int k2d_decode_actions(const k2d_caps* caps, const int32_t* discrete_dev, float* actions_dev, size_t n_rows,
+                       void* stream) {
+  if (!caps || !discrete_dev || !actions_dev) return K2D_E_ARG;
+  if (caps_class(caps) < 0) return K2D_E_CAP;
+  const int A = caps->n_joints + caps->n_thrusters;
+  const size_t n = n_rows * (size_t)A;
+  if (n == 0) return K2D_OK;
+  hipLaunchKernelGGL(k2d_decode_actions_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), discrete_dev, actions_dev, n, caps->n_joints, A);
   return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
 }
 

@@ -215,6 +215,36 @@ def test_reward_and_termination(cfg, n, steps):
     assert n_done > 0 and n_dense > n
 
 
+@pytest.mark.parametrize("cfg,n,steps", [(4, 131, 30), (1, 67, 20), (3, 67, 10)])
+def test_entity_observation_and_masks(cfg, n, steps):
+    """k2d_read_entities against the numpy oracle built on the engine oracle's flat observation: exact."""
+    from oracle import k2d_env
+    b, o, caps = _both(cfg, n, steps)
+    _, _, sc = scenegen.make_scene(cfg, n_envs=n)
+    ref = k2d_env.entities(o.obs(), sc, o.get("shape_adj"), caps)
+    got = b.read_entities()
+    for k, v in ref.items():
+        g = got[k].cpu().numpy()
+        if k == "masks":
+            g = g.view(np.uint32)
+        assert g.shape == v.shape, k
+        assert np.array_equal(g, v), k
+    assert (ref["masks"][:, 3] != 0).any() and (ref["masks"][:, 2] != ref["masks"][:, 1]).any() or cfg != 4
+
+
+def test_multi_discrete_action_decoding():
+    import torch
+    import paper_2410_23208_amd as k2d
+    from oracle import k2d_env
+    caps = scenegen.CAPS["L"]
+    _, prm, sc = scenegen.make_scene(2, n_envs=5)
+    b = k2d.Batch(caps, 5, prm)
+    rng = np.random.default_rng(3)
+    d = rng.integers(0, 3, size=(7, 5, caps[2] + caps[3])).astype(np.int32)
+    out = b.decode_actions(torch.from_numpy(d).cuda()).cpu().numpy()
+    assert np.array_equal(out, k2d_env.decode_actions(d, caps[2], caps[3]))
+
+
 # ------------------------------------------------------------------------------------------ edge cases
 def _hand_scene_parity(sb, prm, steps, n_envs=1):
     sc = sb.scene()

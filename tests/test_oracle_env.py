@@ -86,3 +86,47 @@ def test_distance_is_the_smallest_over_pairs_and_zero_without_a_pair():
     pc[0, pair_index(0, 1, N)] = 2                             # touching something that is not blue or red
     r, done, d = k2d_env.outcome(pos, role, active, pc, np.array([2.0], dtype=np.float32), 1.0, GREEN, BLUE, RED)
     assert done[0] == 0
+
+
+# ------------------------------------------------------------------ entity observation, action decoding
+def test_entity_observation_on_a_hand_built_chain():
+    """Three shapes in a chain a - b - c (two joints) and a loose fourth: one-hots, the two views of a joint,
+    and the masks (direct neighbours vs. everything reachable over joints)."""
+    caps = (2, 2, 2, 1)
+    sb = SceneBuilder(caps)
+    a = sb.box(0.3, 0.2, (0.0, 1.0), role=1)
+    tri = sb.polygon(np.array([[-0.3, -0.1], [0.3, -0.1], [0.0, 0.2]]), (0.5, 1.0), role=3)   # centred on its centroid
+    c = sb.circle(0.15, (1.0, 1.0), role=2)
+    loose = sb.circle(0.1, (3.0, 3.0))
+    sb.joint(a, tri, (0.25, 1.0), motor_on=True, speed=2.0, power=0.5)
+    sb.joint(tri, c, (0.75, 1.0), fixed=True)
+    sb.thruster(c, (0.05, 0.0), angle=0.3, power=1.5)
+    sc = sb.scene(f32=True)
+    o = Oracle(caps, 1, params(gravity_y=0.0), "f32")
+    o.load_scene(sc)
+    ent = k2d_env.entities(o.obs(), sc, o.get("shape_adj"), caps)
+    S = ent["shapes"][0]
+    assert S.shape == (4, 30)
+    assert list(S[a, 8:12]) == [0, 1, 0, 0] and list(S[tri, 8:12]) == [0, 0, 0, 1] and list(S[c, 8:12]) == [0, 0, 1, 0]
+    assert list(S[a, 16:18]) == [0, 1] and list(S[c, 16:18]) == [1, 0]           # circle, polygon
+    assert list(S[a, 27:29]) == [0, 1] and list(S[tri, 27:29]) == [1, 0]         # triangle, rectangle
+    assert S[c, 18] == np.float32(0.15) and S[a, 18] == 0 and (S[c, 19:29] == 0).all()
+    assert S[a, 0] == 0.0 and S[a, 1] == 1.0 and (S[:, 29] == 1).all()
+    J = ent["joints"][0]
+    assert list(ent["joint_idx"][0, 0]) == [a, tri] and list(ent["joint_idx"][0, 1]) == [tri, a]
+    assert np.array_equal(J[0, 2:4], J[1, 4:6]) and np.array_equal(J[0, 4:6], J[1, 2:4])
+    assert J[0, 9] == -J[1, 9] and J[0, 10] == J[1, 10] and J[0, 8] == 1 and J[2, 1] == 1
+    assert list(ent["thruster_idx"][0]) == [c] and ent["thrusters"][0, 0, 3] == np.float32(1.5)
+    M = ent["masks"][0]
+    bit = lambda *idx: sum(1 << i for i in idx)
+    assert list(M[0]) == [bit(a, tri, c, loose)] * 4
+    assert list(M[1]) == [bit(a, tri), bit(a, tri, c), bit(tri, c), bit(loose)]
+    assert list(M[2]) == [bit(a, tri, c)] * 3 + [bit(loose)]
+    assert list(M[3]) == [0, 0, 0, 0]
+
+
+def test_multi_discrete_actions():
+    d = np.array([[[0, 1, 2, 0, 1], [2, 2, 1, 1, 0]]])
+    out = k2d_env.decode_actions(d, 3, 2)
+    assert out.dtype == np.float32
+    assert out.tolist() == [[[0.0, 1.0, -1.0, 0.0, 1.0], [-1.0, -1.0, 1.0, 1.0, 0.0]]]
