@@ -677,6 +677,8 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     if (!(f2i(E[L.shape_flags + i]) & 1) || (E[L.inv_mass + i] == 0.f && E[L.inv_inertia + i] == 0.f))
       static_mask |= 1u << i;
   const bool ja_fix = (static_mask >> ja) & 1u, jb_fix = (static_mask >> jb) & 1u;
+  // where a joint's velocity results go: the shape, or the dump slot if no impulse moves it
+  const int jsa = ja_fix ? K::X_DUMP - L.vel_x : ja, jsb = jb_fix ? K::X_DUMP - L.vel_x : jb;
   // dependency levels of the joints: a joint runs one level after the last earlier joint that shares a
   // movable shape with it, so joints sharing a shape keep their index order, the others run side by side
   int j_level = 0, n_levels = 0;
@@ -1065,16 +1067,12 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
               wa = wa + j_iia * j_acca;
               wb = wb - j_iib * j_acca;
             }
-            if (!ja_fix) {
-              E[L.vel_x + ja] = fmaf(j_ima, j_accx, E[L.vel_x + ja]);
-              E[L.vel_y + ja] = fmaf(j_ima, j_accy, E[L.vel_y + ja]);
-              E[L.omega + ja] = fmaf(j_iia, cross2(j_rax, j_ray, j_accx, j_accy), wa);
-            }
-            if (!jb_fix) {
-              E[L.vel_x + jb] = fmaf(j_imb, -j_accx, E[L.vel_x + jb]);
-              E[L.vel_y + jb] = fmaf(j_imb, -j_accy, E[L.vel_y + jb]);
-              E[L.omega + jb] = fmaf(j_iib, cross2(j_rbx, j_rby, -j_accx, -j_accy), wb);
-            }
+            E[L.vel_x + jsa] = fmaf(j_ima, j_accx, E[L.vel_x + ja]);
+            E[L.vel_y + jsa] = fmaf(j_ima, j_accy, E[L.vel_y + ja]);
+            E[L.omega + jsa] = fmaf(j_iia, cross2(j_rax, j_ray, j_accx, j_accy), wa);
+            E[L.vel_x + jsb] = fmaf(j_imb, -j_accx, E[L.vel_x + jb]);
+            E[L.vel_y + jsb] = fmaf(j_imb, -j_accy, E[L.vel_y + jb]);
+            E[L.omega + jsb] = fmaf(j_iib, cross2(j_rbx, j_rby, -j_accx, -j_accy), wb);
           }
           wave_sync();
         }
@@ -1108,8 +1106,8 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
             apply_impulse(vax, vay, wa, j_ima, j_iia, jx, jy, j_rax, j_ray);
             apply_impulse(vbx, vby, wb, j_imb, j_iib, -jx, -jy, j_rbx, j_rby);
             j_accx = j_accx + jx; j_accy = j_accy + jy;
-            if (!ja_fix) { E[L.vel_x + ja] = vax; E[L.vel_y + ja] = vay; E[L.omega + ja] = wa; }
-            if (!jb_fix) { E[L.vel_x + jb] = vbx; E[L.vel_y + jb] = vby; E[L.omega + jb] = wb; }
+            E[L.vel_x + jsa] = vax; E[L.vel_y + jsa] = vay; E[L.omega + jsa] = wa;
+            E[L.vel_x + jsb] = vbx; E[L.vel_y + jsb] = vby; E[L.omega + jsb] = wb;
           }
           wave_sync();
         }
