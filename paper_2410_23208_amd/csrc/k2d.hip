@@ -143,7 +143,7 @@ struct Cfg {
   static constexpr int X_DUMP = X_STAGE;                   // (once the staged manifolds are taken) 2N+1 words that swallow the
                                                            // velocity stores of shapes no impulse moves (offsets 0, N, 2N)
   static constexpr int X_POOL = X_STAGE + NREG * kManW;
-  static_assert(NREG * kManW >= 2 * N + 1, "dump slots do not fit the staging area");
+  static_assert(NREG * kManW >= 2 * N + 1 && L.pos_x == 0 && L.pos_y == N, "dump slots do not fit the staging area");
   static constexpr int LDS_WORDS = X_POOL + POOL * kRecW;
   // stride = odd multiple of G words: the same word of different environments falls into different banks
   static constexpr int LDS_STRIDE = align_up(LDS_WORDS - G, 2 * G) + G;
@@ -1153,14 +1153,12 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         // the pair's accumulated impulses wait in the HBM record for the next substep (A.7)
         if (env_ok) *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(a, b)) = lam;
         const float ima = E[L.inv_mass + a], imb = E[L.inv_mass + b];
-        if (!((static_mask >> a) & 1u)) {
-          E[L.pos_x + a] = E[L.pos_x + a] - (ima * corr) * nx;
-          E[L.pos_y + a] = E[L.pos_y + a] - (ima * corr) * ny;
-        }
-        if (!((static_mask >> b) & 1u)) {
-          E[L.pos_x + b] = E[L.pos_x + b] + (imb * corr) * nx;
-          E[L.pos_y + b] = E[L.pos_y + b] + (imb * corr) * ny;
-        }
+        // (the positions of shapes no impulse moves go to the dump slot: L.pos_x is word 0 of the image)
+        const int da = ((static_mask >> a) & 1u) ? K::X_DUMP : a, db = ((static_mask >> b) & 1u) ? K::X_DUMP : b;
+        E[L.pos_x + da] = E[L.pos_x + a] - (ima * corr) * nx;
+        E[L.pos_y + da] = E[L.pos_y + a] - (ima * corr) * ny;
+        E[L.pos_x + db] = E[L.pos_x + b] + (imb * corr) * nx;
+        E[L.pos_y + db] = E[L.pos_y + b] + (imb * corr) * ny;
       };
       for_each_level([&](typename S::Own& o) {
                        correct(o.rc.nx, o.rc.ny, o.rc.corr, o.rc.ab,
@@ -1182,14 +1180,11 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
           float xbx = E[L.pos_x + jb] + fmaf(cb, j_abx, -(sb * j_aby)), xby = E[L.pos_y + jb] + fmaf(sb, j_abx, cb * j_aby);
           float cf = prm.joint_beta / (j_ima + j_imb);
           float cx = cf * (xax - xbx), cy = cf * (xay - xby);
-          if (!ja_fix) {
-            E[L.pos_x + ja] = E[L.pos_x + ja] - j_ima * cx;
-            E[L.pos_y + ja] = E[L.pos_y + ja] - j_ima * cy;
-          }
-          if (!jb_fix) {
-            E[L.pos_x + jb] = E[L.pos_x + jb] + j_imb * cx;
-            E[L.pos_y + jb] = E[L.pos_y + jb] + j_imb * cy;
-          }
+          const int da = ja_fix ? K::X_DUMP : ja, db = jb_fix ? K::X_DUMP : jb;
+          E[L.pos_x + da] = E[L.pos_x + ja] - j_ima * cx;
+          E[L.pos_y + da] = E[L.pos_y + ja] - j_ima * cy;
+          E[L.pos_x + db] = E[L.pos_x + jb] + j_imb * cx;
+          E[L.pos_y + db] = E[L.pos_y + jb] + j_imb * cy;
         }
         wave_sync();
       }
