@@ -465,6 +465,64 @@ def make_scene(cfg_id, n_envs=None, env_ids=None, episode=0, seed=SEED):
     return caps, params, to_f32(sc)
 
 
+def make_stack_scene(n_envs=None, env_ids=None, episode=0, seed=SEED, n_substeps=3, n_iters=10):
+    """A stacking workload (the case Appendix A.7 describes: rectangles resting on top of each other, where
+    solving one contact disturbs its neighbours): L capacities, the floor and two walls, nine boxes piled
+    into one, two or three towers with a little sideways jitter, four balls resting on the floor.  No joint,
+    no thruster.  Long dependency chains are the worst case of a level-by-level constraint sweep.
+    Returns (caps, params, scene) like make_scene."""
+    caps = CAPS["L"]
+    P, C, J, T = caps
+    N = P + C
+    if env_ids is None:
+        env_ids = np.arange(1024 if n_envs is None else n_envs)
+    env_ids = np.asarray(env_ids)
+    E = len(env_ids)
+    d = Draws(seed, 5, episode, env_ids)
+    sc = empty_scene(caps, E)
+    sc["friction"][:] = 0.6
+    sc["density"][:] = 1.0
+    half = np.zeros((E, P, 2))
+    half[:, 0] = (5.0, 0.1)
+    half[:, 1] = half[:, 2] = (0.1, 5.0)
+    sc["pos"][:, 0] = (2.5, 0.0)
+    sc["pos"][:, 1] = (-2.6, 5.0)
+    sc["pos"][:, 2] = (7.6, 5.0)
+    n_towers = 1 + d.integers(3)                                  # 1..3 towers
+    tower = np.minimum((d.u(9) * n_towers[:, None]).astype(np.int64), n_towers[:, None] - 1)
+    tower[:, 0] = 0
+    hx = d.u(9, lo=0.3, hi=0.5)
+    hy = d.u(9, lo=0.1, hi=0.25)
+    jitter = d.u(9, lo=-0.05, hi=0.05)
+    top = np.full((E, 3), 0.1)                                    # the floor's upper face
+    for q in range(9):
+        i = 3 + q
+        t = tower[:, q]
+        half[:, i, 0], half[:, i, 1] = hx[:, q], hy[:, q]
+        y = top[np.arange(E), t] + hy[:, q] + 0.001
+        sc["pos"][:, i, 0] = 0.5 + 1.6 * t + jitter[:, q]
+        sc["pos"][:, i, 1] = y
+        top[np.arange(E), t] = y + hy[:, q]
+    for i in range(P):
+        sc["verts"][:, i] = np.stack([-half[:, i, 0], -half[:, i, 1], half[:, i, 0], -half[:, i, 1],
+                                      half[:, i, 0], half[:, i, 1], -half[:, i, 0], half[:, i, 1]], -1).reshape(E, 4, 2)
+    sc["n_verts"][:] = 4
+    area = 4.0 * half[..., 0] * half[..., 1]
+    inertia = area * (4.0 * half[..., 0] ** 2 + 4.0 * half[..., 1] ** 2) / 12.0
+    sc["inv_mass"][:, 3:P] = 1.0 / area[:, 3:]
+    sc["inv_inertia"][:, 3:P] = 1.0 / inertia[:, 3:]
+    r = d.u(C, lo=0.15, hi=0.3)
+    sc["radius"][:] = r
+    sc["pos"][:, P:, 0] = 5.2 + 0.65 * np.arange(C)[None, :]
+    sc["pos"][:, P:, 1] = 0.1 + r + 0.001
+    im, ii = circle_mass_props(r, np.ones_like(r))
+    sc["inv_mass"][:, P:] = im
+    sc["inv_inertia"][:, P:] = ii
+    sc["active"][:] = 1
+    sc["role"] = d.integers(4, N)
+    return caps, default_params(n_substeps, n_iters), to_f32(sc)
+
+
 def make_actions(cfg_id, n_steps, n_envs, seed=SEED, step0=0):
     """Actions U[-1,1], fp32 values, shape [n_steps, n_envs, J+T]; independent per (step, env)."""
     caps = CAPS[CONFIGS[cfg_id]["size"]]

@@ -64,6 +64,18 @@ def test_bit_identical_other_episodes(cfg, episode, n, steps):
     assert (os_["pair_count"] > 0).sum() > n
 
 
+def test_stacking_workload_bit_identical():
+    """Towers of up to nine boxes: dependency chains as long as a tower is high."""
+    caps, prm, sc = scenegen.make_stack_scene(n_envs=131)
+    act = np.zeros((96, 131, caps[2] + caps[3]), dtype=np.float32)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b = parity.run_gpu(caps, prm, sc, act)
+    gs, os_ = b.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    assert ((os_["pair_count"] > 0).sum(1) == 13).all()
+
+
 def test_contacts_and_observation_outputs():
     b, o, caps = _both(3, 131, 40)
     pc, adj = b.read_contacts()

@@ -599,3 +599,28 @@ def test_limited_pendulum_stays_within_its_range():
     o2.step(np.zeros((60, 1, 1)))
     th = o2.state()["theta"][0]
     assert th[top] - th[bar] > 1.0
+
+
+# ------------------------------------------------------------------ stacking (A.7)
+def test_towers_of_boxes_stand_and_warm_starting_is_what_holds_them():
+    """The stacking workload: up to nine boxes on top of each other.  With warm starting (A.7) the towers
+    stand for 256 steps -- millimetres of sideways drift, a settling of the order of the slop per contact,
+    velocities of millimetres per second; without it the same sweeps leave them sagging and jittering."""
+    import scenegen
+    caps, prm, sc = scenegen.make_stack_scene(n_envs=48)
+    act = np.zeros((256, 48, caps[2] + caps[3]))
+    p0 = np.asarray(sc["pos"])[:, 3:12]
+
+    def settle(p):
+        o, _ = run(sc, p, caps=caps, dtype="f32")
+        o.step(act, n_threads=4)
+        st = o.state()
+        pos = st["pos"].reshape(48, -1, 2)[:, 3:12]
+        return (np.abs(pos[..., 0] - p0[..., 0]).max(), (p0[..., 1] - pos[..., 1]).max(),
+                np.abs(st["vel"]).max(), (st["pair_count"] > 0).sum(1))
+
+    dx, dy, v, pairs = settle(prm)
+    assert dx < 0.01 and 0.0 < dy < 0.03 and v < 0.02
+    assert (pairs == 13).all()                       # 9 box contacts in the towers + 4 balls on the floor
+    dx0, dy0, v0, _ = settle(dict(prm, warm_start=0))
+    assert dy0 > 2 * dy and v0 > 5 * v
