@@ -130,3 +130,24 @@ def test_multi_discrete_actions():
     out = k2d_env.decode_actions(d, 3, 2)
     assert out.dtype == np.float32
     assert out.tolist() == [[[0.0, 1.0, -1.0, 0.0, 1.0], [-1.0, -1.0, 1.0, 1.0, 0.0]]]
+
+
+def test_observation_widths_match_the_papers_tables():
+    """Tables 5-7 fix which fields an entity carries and how wide each is."""
+    import os
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "tables5to7_observation_fields.txt"))
+            if l.strip() and not l.startswith("#")]
+    sym = {"n_roles": k2d_env.N_ROLES, "n_types": 2, "n_colours": 0}     # joint colours are not engine state
+    width = {}
+    for table, _, dims in rows:
+        width[table] = width.get(table, 0) + (sym[dims] if dims in sym else int(dims))
+    assert k2d_env.SHAPE_DIM == width["shape"] + 1                       # + the active flag (the set's mask)
+    assert k2d_env.JOINT_DIM == width["joint"] and k2d_env.THRUSTER_DIM == width["thruster"]
+    # the engine's flat observation: the same fields without one-hots (role passed through, n_verts for the
+    # polygon kind, an active flag per shape)
+    for caps in ((5, 2, 1, 1), (12, 4, 6, 2)):
+        P, C, J, T = caps
+        o = Oracle(caps, 1, params(), "f32")
+        per_poly = width["shape"] - sym["n_roles"] - sym["n_types"] - 1 - 2 + 1 + 1 + 1   # no radius, n_verts, active, role
+        per_circ = width["shape"] - sym["n_roles"] - sym["n_types"] - 8 - 2 + 1 + 1        # no vertices, active, role
+        assert o.obs().shape[1] == P * per_poly + C * per_circ + J * width["joint"] + T * width["thruster"]
