@@ -18,10 +18,16 @@
 // Pins (tests/test_oracle_*.py): closed-form free fall under semi-implicit Euler, head-on circle
 // collisions with restitution, box resting on a floor, energy non-increase without actuation,
 // pendulum drift and period, motor tanh law, thruster closed form, warm-start bookkeeping, brute-force
-// point-sampled overlap for the narrowphase, hand-evaluated manifolds, round-parallel == sequential.
+// point-sampled overlap for the narrowphase, hand-evaluated manifolds, round-parallel == sequential,
+// joint limits (closed form of one visit, symmetry, restoring motion untouched), towers of boxes standing.
 // Unpinned by the paper (no values printed there): the coefficients alpha, beta, gamma, rho, the
 // penetration slop, the restitution threshold and the reference-face tie margin; they are pinned only
 // through the invariants above ("parity unpinned" for their numeric values).
+//
+// Rounding: the paper gives formulas, not the rounding of their evaluation.  Here two-term products (dot
+// and cross products, rotations, "v + j/m", the relative velocity of A.3.5) are evaluated with one fused
+// multiply-add, everything else one operation at a time (built with -ffp-contract=off); sin, cos and
+// tanh in fp32 are fixed operation sequences of their own.
 
 #include <algorithm>
 #include <cmath>
