@@ -19,7 +19,9 @@
 // collisions with restitution, box resting on a floor, energy non-increase without actuation,
 // pendulum drift and period, motor tanh law, thruster closed form, warm-start bookkeeping, brute-force
 // point-sampled overlap for the narrowphase, hand-evaluated manifolds, round-parallel == sequential,
-// joint limits (closed form of one visit, symmetry, restoring motion untouched), towers of boxes standing.
+// joint limits (closed form of one visit, symmetry, restoring motion untouched), towers of boxes standing,
+// batched impulse resolution (closed form of two constraints on one body solved in one batch, batch size 1
+// == sequential, momentum, the stability trade-off of A.8 on the towers).
 // Unpinned by the paper (no values printed there): the coefficients alpha, beta, gamma, rho, the
 // penetration slop, the restitution threshold and the reference-face tie margin; they are pinned only
 // through the invariants above ("parity unpinned" for their numeric values).
@@ -61,8 +63,9 @@ struct Params {
   double joint_beta = 0.2;             // joint positional correction                     (A.4.1)
   double tie_eps = 1e-3;               // reference face goes to b only if sep_b > sep_a + tie_eps
   int order_mode = 0;                  // 0: canonical sequential; 1: each round from a snapshot (test)
+  int batch_size = 0;                  // 0: sequential sweep; B >= 1: batched impulse resolution (A.8)
 };
-constexpr int kNumParams = 16;
+constexpr int kNumParams = 17;
 
 template <class R>
 struct V2 {
@@ -440,33 +443,74 @@ inline bool joint_live(const Env<R>& E, const Joint<R>& j) {
   return j.a != j.b && a.active && b.active && (a.inv_mass + b.inv_mass) > R(0);
 }
 
+// One manifold point of a colliding pair: normal impulse then friction impulse (A.3.5, A.3.6), each
+// accumulated and clamped (A.7), applied to the bodies a and b that the caller hands in.  `j` and `jf`
+// return the two impulses that a received (b received the opposite ones).
+template <class R>
+void solve_contact_point(Body<R>& a, Body<R>& b, const ContactPair<R>& cp, int k, ContactAcc<R>& acc, V2<R>& j,
+                         V2<R>& jf) {
+  const ContactRow<R>& row = cp.row[k];
+  // normal impulse (A.3.5) with the velocity correction added to the numerator (A.3.7),
+  // accumulated and kept non-negative (A.7)
+  R vn = dot(cp.n, rel_vel(a, row.ra, b, row.rb));
+  R dl = row.mass_n * (vn + row.rest + row.bias);
+  R ln = std::max(acc.lambda_n[k] + dl, R(0));
+  dl = ln - acc.lambda_n[k];
+  acc.lambda_n[k] = ln;
+  j = (-dl) * cp.n;   // impulse on a; b receives the opposite
+  apply_impulse(a, j, row.ra);
+  apply_impulse(b, V2<R>{-j.x, -j.y}, row.rb);
+  // friction impulse (A.3.6), clipped to +-mu * accumulated normal impulse
+  R vt = dot(cp.t, rel_vel(a, row.ra, b, row.rb));
+  R dt_ = -row.mass_t * vt;
+  R lim = cp.mu * ln;
+  R lt = std::min(std::max(acc.lambda_t[k] + dt_, -lim), lim);
+  dt_ = lt - acc.lambda_t[k];
+  acc.lambda_t[k] = lt;
+  jf = dt_ * cp.t;
+  apply_impulse(a, jf, row.ra);
+  apply_impulse(b, V2<R>{-jf.x, -jf.y}, row.rb);
+}
+
 template <class R>
 void solve_contact_pair(Env<R>& E, ContactPair<R>& cp, ContactAcc<R>& acc) {
-  Body<R>& a = E.bodies[cp.a];
-  Body<R>& b = E.bodies[cp.b];
-  for (int k = 0; k < 2; ++k) {
-    ContactRow<R>& row = cp.row[k];
-    if (!row.active) continue;
-    // normal impulse (A.3.5) with the velocity correction added to the numerator (A.3.7),
-    // accumulated and kept non-negative (A.7)
-    R vn = dot(cp.n, rel_vel(a, row.ra, b, row.rb));
-    R dl = row.mass_n * (vn + row.rest + row.bias);
-    R ln = std::max(acc.lambda_n[k] + dl, R(0));
-    dl = ln - acc.lambda_n[k];
-    acc.lambda_n[k] = ln;
-    V2<R> j = (-dl) * cp.n;   // impulse on a; b receives the opposite
-    apply_impulse(a, j, row.ra);
-    apply_impulse(b, V2<R>{-j.x, -j.y}, row.rb);
-    // friction impulse (A.3.6), clipped to +-mu * accumulated normal impulse
-    R vt = dot(cp.t, rel_vel(a, row.ra, b, row.rb));
-    R dt_ = -row.mass_t * vt;
-    R lim = cp.mu * ln;
-    R lt = std::min(std::max(acc.lambda_t[k] + dt_, -lim), lim);
-    dt_ = lt - acc.lambda_t[k];
-    acc.lambda_t[k] = lt;
-    V2<R> jf = dt_ * cp.t;
-    apply_impulse(a, jf, row.ra);
-    apply_impulse(b, V2<R>{-jf.x, -jf.y}, row.rb);
+  V2<R> j, jf;
+  for (int k = 0; k < 2; ++k)
+    if (cp.row[k].active) solve_contact_point(E.bodies[cp.a], E.bodies[cp.b], cp, k, acc, j, jf);
+}
+
+// Batched impulse resolution (A.8): the manifold points -- two per shape pair, pairs in canonical order --
+// are dealt in turn over n_b = ceil(points / B) batches, so that neighbouring points (which tend to be
+// active together) land in different batches and a batch holds at most B points.  The batches are
+// solved one after the other; the active points of one batch are all solved from the velocities the
+// batch started with, each on its own copy of its two bodies, and their impulses are then applied
+// to the bodies in point order.  B = 1 is the sequential sweep; B >= points solves every point in
+// parallel.
+template <class R>
+void solve_contacts_batched(Env<R>& E, std::vector<ContactPair<R>>& cps, int N, int B) {
+  struct Pending { int z, k; V2<R> j, jf; };
+  const int n_points = 2 * (int)cps.size();
+  const int n_b = (n_points + B - 1) / B;
+  std::vector<Pending> pend;
+  for (int b = 0; b < n_b; ++b) {
+    pend.clear();
+    for (int s = b; s < n_points; s += n_b) {
+      const int z = s / 2, k = s % 2;
+      ContactPair<R>& cp = cps[z];
+      if (!cp.row[k].active) continue;
+      Body<R> a = E.bodies[cp.a], bb = E.bodies[cp.b];   // private copies: the batch's starting velocities
+      Pending p{z, k, {0, 0}, {0, 0}};
+      solve_contact_point(a, bb, cp, k, E.acc[pair_index(cp.a, cp.b, N)], p.j, p.jf);
+      pend.push_back(p);
+    }
+    for (const Pending& p : pend) {
+      const ContactPair<R>& cp = cps[p.z];
+      const ContactRow<R>& row = cp.row[p.k];
+      apply_impulse(E.bodies[cp.a], p.j, row.ra);
+      apply_impulse(E.bodies[cp.b], V2<R>{-p.j.x, -p.j.y}, row.rb);
+      apply_impulse(E.bodies[cp.a], p.jf, row.ra);
+      apply_impulse(E.bodies[cp.b], V2<R>{-p.jf.x, -p.jf.y}, row.rb);
+    }
   }
 }
 
@@ -694,7 +738,9 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
   for (int it = 0; it < P.n_iters; ++it) {
     for (int q = 0; q < nJ; ++q)
       if (jrs[q].live) solve_joint(E, E.joints[q], jrs[q]);
-    if (P.order_mode == 0) {
+    if (P.batch_size > 0) {
+      solve_contacts_batched(E, cps, N, P.batch_size);
+    } else if (P.order_mode == 0) {
       for (ContactPair<R>& cp : cps)
         if (cp.any) solve_contact_pair(E, cp, E.acc[pair_index(cp.a, cp.b, N)]);
     } else {
@@ -1001,7 +1047,8 @@ void* ko_create(int P, int C, int J, int T, int n_envs, int use_double) {
 void ko_destroy(void* h) { delete static_cast<BatchBase*>(h); }
 
 // params: [dt, gravity_y, n_substeps, n_iters, warm_start, alpha, beta, gamma, rho, slop,
-//          restitution_threshold, clip_thruster_01, joint_alpha, joint_beta, tie_eps, order_mode]
+//          restitution_threshold, clip_thruster_01, joint_alpha, joint_beta, tie_eps, order_mode,
+//          batch_size]
 int ko_set_params(void* h, const double* p, int n) {
   if (!h || !p || n != kNumParams) return -1;
   Params& q = static_cast<BatchBase*>(h)->params;
@@ -1009,7 +1056,8 @@ int ko_set_params(void* h, const double* p, int n) {
   q.alpha = p[5]; q.beta = p[6]; q.gamma = p[7]; q.rho = p[8]; q.slop = p[9];
   q.restitution_threshold = p[10]; q.clip_thruster_01 = (int)p[11];
   q.joint_alpha = p[12]; q.joint_beta = p[13]; q.tie_eps = p[14]; q.order_mode = (int)p[15];
-  if (q.n_substeps < 1 || q.n_iters < 0) return -2;
+  q.batch_size = (int)p[16];
+  if (q.n_substeps < 1 || q.n_iters < 0 || q.batch_size < 0) return -2;
   return 0;
 }
 long ko_field_size(void* h, const char* f) { return static_cast<BatchBase*>(h)->field_size(f); }

@@ -624,3 +624,102 @@ def test_towers_of_boxes_stand_and_warm_starting_is_what_holds_them():
     assert (pairs == 13).all()                       # 9 box contacts in the towers + 4 balls on the floor
     dx0, dy0, v0, _ = settle(dict(prm, warm_start=0))
     assert dy0 > 2 * dy and v0 > 5 * v
+
+
+# ------------------------------------------------------------------ batched impulse resolution (A.8)
+def _wedge(batch_size):
+    """A frictionless ball touching both faces of a V of two static slabs, moving into the corner."""
+    sb = SceneBuilder(CAPS)
+    r, pen, hy, c = 0.5, 0.002, 0.3, np.array([0.2, 1.0])
+    normals = []
+    for phi in (np.deg2rad(30.0), np.deg2rad(-30.0)):
+        n = np.array([-np.sin(phi), np.cos(phi)])
+        sb.box(3.0, hy, tuple(c - (r - pen + hy) * n), theta=phi, static=True, friction=0.0)
+        normals.append(n)
+    ball = sb.circle(r, tuple(c), vel=(0.3, -0.4), friction=0.0)
+    p = params(n_iters=1, gravity_y=-9.81, warm_start=0, batch_size=batch_size)
+    o, sc = run(sb, p, f32_inputs=False)
+    o.step(zeros_actions(1, 1, CAPS))
+    st = o.state()
+    v0 = np.array([0.3, -0.4 - 9.81 * p["dt"]])
+    return st["vel"].reshape(-1, 2)[ball], v0, normals
+
+
+def test_batched_resolution_closed_form_in_a_wedge():
+    """Two active constraints on one body.  Solved one after the other (batch size 1) the second sees the
+    velocity the first left; solved in one batch both see the starting velocity and their impulses add."""
+    def project(v, n):
+        return v - min(v @ n, 0.0) * n
+
+    v_seq, v0, (n1, n2) = _wedge(1)
+    v_ref, _, _ = _wedge(0)
+    assert np.array_equal(v_seq, v_ref)
+    orders = [project(project(v0, n1), n2), project(project(v0, n2), n1)]
+    assert min(np.abs(v_seq - w).max() for w in orders) < 1e-12
+    v_par, _, _ = _wedge(1000)
+    jacobi = v0 - min(v0 @ n1, 0.0) * n1 - min(v0 @ n2, 0.0) * n2
+    assert np.abs(v_par - jacobi).max() < 1e-12
+    assert min(np.abs(jacobi - w).max() for w in orders) > 0.05     # the two answers are far apart
+
+
+def test_batch_size_one_is_the_sequential_sweep():
+    caps, p, sc = scenegen.make_scene(3, n_envs=16)
+    act = scenegen.make_actions(3, 30, 16)
+    out = []
+    for B in (0, 1, 16):
+        o = Oracle(caps, 16, dict(p, batch_size=B), "f32")
+        o.load_scene(sc)
+        o.step(act)
+        out.append(o.state())
+    assert out[0]["pair_count"].sum() > 16 * 3
+    for k in ("pos", "theta", "vel", "omega", "lambda_n", "lambda_t", "joint_acc", "pair_count"):
+        assert np.array_equal(out[0][k], out[1][k]), k
+    assert not np.array_equal(out[0]["vel"], out[2]["vel"])
+
+
+def test_batched_resolution_conserves_momentum():
+    """Every impulse of a batch is applied to a and, reversed, to b: three bodies hitting each other at once,
+    all points in one batch, keep their total linear and angular momentum."""
+    sb = SceneBuilder(CAPS)
+    ids = [sb.box(0.5, 0.2, (0.0, 0.0), theta=0.3, restitution=0.4),
+           sb.circle(0.2, (0.3, 0.8), vel=(0.2, -3.0), restitution=0.6),
+           sb.circle(0.25, (-0.35, -0.75), vel=(0.5, 2.5), restitution=0.2)]
+    o, sc = run(sb, params(gravity_y=0.0, alpha=0.0, beta=0.0, batch_size=1000))
+
+    def momenta(st):
+        m = 1 / sc["inv_mass"][0, ids]
+        I = 1 / sc["inv_inertia"][0, ids]
+        pos = st["pos"].reshape(-1, 2)[ids]
+        v = st["vel"].reshape(-1, 2)[ids]
+        w = st["omega"][0, ids]
+        return (m[:, None] * v).sum(0), (m * (pos[:, 0] * v[:, 1] - pos[:, 1] * v[:, 0]) + I * w).sum()
+
+    p0, L0 = momenta(o.state())
+    o.step(zeros_actions(30, 1, CAPS))
+    p1, L1 = momenta(o.state())
+    assert abs(o.state()["omega"][0, ids[0]]) > 1e-3
+    assert np.allclose(p0, p1, atol=1e-12) and L1 == pytest.approx(L0, abs=1e-12)
+
+
+def test_towers_show_the_stability_trade_off_of_the_batch_size():
+    """A.8: solving every collision constraint in parallel noticeably reduces stability, batches of 16
+    keep the speed-up without that cost.  On the towers of boxes: batches of up to 16 points stand like the
+    sequential sweep, larger batches jitter, one batch of everything blows the towers apart."""
+    caps, prm, sc = scenegen.make_stack_scene(n_envs=48)
+    act = np.zeros((256, 48, caps[2] + caps[3]))
+    p0 = np.asarray(sc["pos"])[:, 3:12]
+
+    def settle(B):
+        o, _ = run(sc, dict(prm, batch_size=B), caps=caps, dtype="f32")
+        o.step(act, n_threads=4)
+        st = o.state()
+        pos = st["pos"].reshape(48, -1, 2)[:, 3:12]
+        return (p0[..., 1] - pos[..., 1]).max(), np.abs(st["vel"]).max()
+
+    dy1, v1 = settle(0)
+    dy16, v16 = settle(16)
+    dy32, v32 = settle(32)
+    dyall, vall = settle(2 * 120)
+    assert dy16 < 1.1 * dy1 and v16 < 0.02
+    assert dy32 > 1.5 * dy1 and v32 > 10 * max(v1, v16)
+    assert vall > 100.0
