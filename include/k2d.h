@@ -53,7 +53,13 @@ typedef struct {
   float joint_alpha;           /* A.4.1 velocity correction of the joint point constraint, 1/s         */
   float joint_beta;            /* A.4.1 positional correction of the joint point constraint            */
   float tie_eps;               /* A.3.4: b's face is the reference face only if it wins by tie_eps     */
+  int32_t batch_size;          /* A.8: 0 = collision constraints one after the other in canonical order */
+                               /* (run level by level, same bits); B in 1..K2D_MAX_BATCH_SIZE = the     */
+                               /* manifold points, two per pair in canonical order, dealt in turn over  */
+                               /* ceil(points / B) batches; a batch is solved from the velocities it    */
+                               /* starts with and its impulses applied in point order (16 in the paper) */
 } k2d_params;
+#define K2D_MAX_BATCH_SIZE 32
 
 /* Word (4-byte) offsets inside one environment record.  A record is an array of 32-bit words, floats
  * unless marked (i) = int32.  Arrays are stored component-major ("structure of arrays" inside the

@@ -157,9 +157,35 @@ struct Params {   // device copy of k2d_params with the substep precomputed
   float alpha, beta, gamma, rho, slop, rest_thr;
   int clip_thr;
   float joint_alpha, joint_beta, tie_eps;
+  int n_batches;   // batched schedule (A.8): batches per sweep of the collision constraints, 0 = not used
 };
 
 __device__ __forceinline__ int f2i(float f) { return __float_as_int(f); }
+
+// Inclusive prefix sum and sum over the 16 lanes of an environment's group (one DPP row: shifts within the
+// row read zero where there is no source lane; rotations reach every lane).
+__device__ __forceinline__ unsigned group_prefix_sum(unsigned v) {
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);
+  return v;
+}
+__device__ __forceinline__ unsigned group_sum(unsigned v) {
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x121, 0xf, 0xf, false);
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x122, 0xf, 0xf, false);
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x124, 0xf, 0xf, false);
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xf, 0xf, false);
+  return v;
+}
+// OR over the 16 lanes of an environment's group (one DPP row: rotations by 1, 2, 4, 8 within the row).
+__device__ __forceinline__ unsigned group_or(unsigned v) {
+  v |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x121, 0xf, 0xf, false);
+  v |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x122, 0xf, 0xf, false);
+  v |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x124, 0xf, 0xf, false);
+  v |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xf, 0xf, false);
+  return v;
+}
 
 // A workgroup of the step kernel is one wavefront, and the memory operations of one wavefront are
 // performed in the order they are issued: lanes that exchange data through LDS need no hardware barrier
@@ -458,6 +484,51 @@ struct Step {
       }
     }
   }
+  // Batched schedule (A.8): point q of a pair solved on private copies of the two bodies' velocities (the
+  // arithmetic of solve_points); returns the normal impulse (jx, jy) and the friction impulse (fx, fy)
+  // that a receives, for the batch to apply afterwards, and the contact arms.  (With more than one batch
+  // the two points of a pair never share a batch, so one visit handles at most one of them: its
+  // constants are picked by q, which keeps the record in registers.)
+  static __device__ __forceinline__ void point_impulses(PairRec& rc, bool q, float ima, float iia, float imb, float iib,
+                                                        float vax, float vay, float wa, float vbx, float vby, float wb,
+                                                        float& jx, float& jy, float& fx, float& fy, float& rax,
+                                                        float& ray, float& rbx, float& rby) {
+    const float tx = -rc.ny, ty = rc.nx;
+    rax = q ? rc.rax[1] : rc.rax[0]; ray = q ? rc.ray[1] : rc.ray[0];
+    rbx = q ? rc.rbx[1] : rc.rbx[0]; rby = q ? rc.rby[1] : rc.rby[0];
+    const float mass_n = q ? rc.mass_n[1] : rc.mass_n[0], mass_t = q ? rc.mass_t[1] : rc.mass_t[0];
+    const float rest = q ? rc.rest[1] : rc.rest[0], bias = q ? rc.bias[1] : rc.bias[0];
+    const float lam_n = q ? rc.lam_n[1] : rc.lam_n[0], lam_t = q ? rc.lam_t[1] : rc.lam_t[0];
+    float rx, ry;
+    rel_vel(vax, vay, wa, rax, ray, vbx, vby, wb, rbx, rby, rx, ry);
+    float vn = dot2(rc.nx, rc.ny, rx, ry);
+    float dl = mass_n * (vn + rest + bias);
+    float ln = fmaxf(lam_n + dl, 0.f);
+    dl = ln - lam_n;
+    jx = (-dl) * rc.nx; jy = (-dl) * rc.ny;
+    apply_impulse(vax, vay, wa, ima, iia, jx, jy, rax, ray);
+    apply_impulse(vbx, vby, wb, imb, iib, -jx, -jy, rbx, rby);
+    rel_vel(vax, vay, wa, rax, ray, vbx, vby, wb, rbx, rby, rx, ry);
+    float vt = dot2(tx, ty, rx, ry);
+    float dt_ = -mass_t * vt;
+    float lim = rc.mu * ln;
+    float lt = fminf(fmaxf(lam_t + dt_, -lim), lim);
+    dt_ = lt - lam_t;
+    fx = dt_ * tx; fy = dt_ * ty;
+    if (q) { rc.lam_n[1] = ln; rc.lam_t[1] = lt; }
+    else { rc.lam_n[0] = ln; rc.lam_t[0] = lt; }
+  }
+  // Where the two points of pair `id` (canonical order) fall in the batched schedule: the points, two per
+  // pair, are dealt in turn over n_b batches.  Returns batch | place<<8 of point 0, the same <<16 of point 1.
+  static __device__ __forceinline__ int batch_places(int id, int n_b) {
+    constexpr int odd = N & 1;   // the phantom's pair (slot 0 of every round) is not a pair
+    const int dense = (id / K::GP) * (K::PPR - odd) + (id % K::GP) - odd;
+    const int s0 = 2 * dense;
+    const int j0 = s0 / n_b, b0 = s0 - j0 * n_b;
+    int b1 = b0 + 1, j1 = j0;
+    if (b1 == n_b) { b1 = 0; j1 = j0 + 1; }
+    return b0 | (j0 << 8) | (b1 << 16) | (j1 << 24);
+  }
   // Warm starting of one pair (A.7): re-apply the kept accumulated impulses.
   static __device__ __forceinline__ void warm_points(const PairRec& rc, float ima, float iia, float imb, float iib,
                                                      float& vax, float& vay, float& wa, float& vbx, float& vby,
@@ -577,7 +648,8 @@ struct Step {
 
 // RESET: after step s an environment e with reset_level[s * n_envs + e] = l >= 0 starts a new episode from
 // record l of `levels` (what k2d_reset does between launches, without leaving the kernel).
-template <class K, bool RESET>
+// BATCHED: the collision constraints of a sweep are solved in the batches of A.8 instead of level by level.
+template <class K, bool RESET, bool BATCHED>
 __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ state, const float* __restrict__ actions,
                                                       int n_envs, int n_steps, Params prm,
                                                       const float* __restrict__ levels, int n_level_records,
@@ -905,12 +977,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       {
         const unsigned m0 = cand & pp_mask, m1 = cand & pc_mask, m2 = cand & ~(pp_mask | pc_mask);
         const unsigned mine = (unsigned)__popc(m0) | ((unsigned)__popc(m1) << 8) | ((unsigned)__popc(m2) << 16);
-        unsigned incl = mine;
-        for (int d = 1; d < G; d <<= 1) {
-          unsigned up = __shfl_up(incl, d, G);
-          if (k >= d) incl += up;
-        }
-        const unsigned tot = __shfl(incl, G - 1, G), excl = incl - mine;
+        const unsigned incl = group_prefix_sum(mine), tot = group_sum(mine), excl = incl - mine;
         kind_n[0] = tot & 255; kind_n[1] = (tot >> 8) & 255; kind_n[2] = (tot >> 16) & 255;
         kind_off[0] = 0; kind_off[1] = kind_n[0]; kind_off[2] = kind_n[0] + kind_n[1];
         int w0 = kind_off[0] + (int)(excl & 255), w1 = kind_off[1] + (int)((excl >> 8) & 255);
@@ -1079,6 +1146,12 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       }
 
       // ---- solver sweeps (Alg. 1): joints, then collisions ----
+      const int n_b = BATCHED ? prm.n_batches : 1;
+      int oa_bj = 0, ob_bj = 0;   // batched schedule: batch and place of the two points of the held pairs
+      if constexpr (BATCHED) {
+        if (oa.id >= 0) oa_bj = S::batch_places(oa.id, n_b);
+        if (ob.id >= 0) ob_bj = S::batch_places(ob.id, n_b);
+      }
       for (int it = 0; it < prm.n_iters; ++it) {
         for (int lv = 0; lv < wave_levels; ++lv) {
           if (k < J && j_live && j_level == lv) {
@@ -1111,6 +1184,90 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
           }
           wave_sync();
         }
+        if constexpr (BATCHED) {
+          // A.8: the points of batch b are solved from the velocities the batch starts with, their impulses
+          // staged by their place in the batch; then lane s applies to shape s, in place order, the
+          // impulses of the points that touch it (so every body sees them in point order).
+          for (int b = 0; b < n_b; ++b) {
+            unsigned pm = 0u;   // places of the batch taken by this lane's points
+            auto stage_point = [&](int j, int ab, float jx, float jy, float fx, float fy, float rax, float ray,
+                                   float rbx, float rby) {
+              LdsF p = to_lds(E + K::X_STAGE + j * K::kManW);
+              p[0] = jx; p[1] = jy; p[2] = fx; p[3] = fy;
+              p[4] = rax; p[5] = ray; p[6] = rbx; p[7] = rby;
+              p[8] = i2f(ab & 0xffff);
+              pm |= 1u << j;
+            };
+            auto own_points = [&](typename S::Own& o, int bj) {
+              if (o.id < 0) return;
+              const bool hit0 = ((o.rc.ab >> 16) & 1) && (bj & 0xff) == b;
+              const bool hit1 = ((o.rc.ab >> 17) & 1) && ((bj >> 16) & 0xff) == b;
+              if (hit0 || hit1) {
+                const float vax = E[L.vel_x + o.pa], vay = E[L.vel_y + o.pa], wa = E[L.omega + o.pa];
+                const float vbx = E[L.vel_x + o.pb], vby = E[L.vel_y + o.pb], wb = E[L.omega + o.pb];
+                float jx, jy, fx, fy, rax, ray, rbx, rby;
+                S::point_impulses(o.rc, hit1, o.ima, o.iia, o.imb, o.iib, vax, vay, wa, vbx, vby, wb, jx, jy, fx, fy,
+                                  rax, ray, rbx, rby);
+                stage_point((bj >> (hit1 ? 24 : 8)) & 0xff, o.rc.ab, jx, jy, fx, fy, rax, ray, rbx, rby);
+              }
+            };
+            own_points(oa, oa_bj);
+            if (any_b) own_points(ob, ob_bj);
+            if (any_listed) {
+              auto listed_points = [&](auto rp) {
+                PairRec rc;
+                rec_load(rp, rc);
+                const int bj = S::batch_places((rc.ab >> 18) & 127, n_b);
+                const bool hit0 = ((rc.ab >> 16) & 1) && (bj & 0xff) == b;
+                const bool hit1 = ((rc.ab >> 17) & 1) && ((bj >> 16) & 0xff) == b;
+                if (hit0 || hit1) {
+                  const int a = rc.ab & 0xff, bb = (rc.ab >> 8) & 0xff;
+                  const float vax = E[L.vel_x + a], vay = E[L.vel_y + a], wa = E[L.omega + a];
+                  const float vbx = E[L.vel_x + bb], vby = E[L.vel_y + bb], wb = E[L.omega + bb];
+                  const float ima = E[L.inv_mass + a], iia = E[L.inv_inertia + a];
+                  const float imb = E[L.inv_mass + bb], iib = E[L.inv_inertia + bb];
+                  float jx, jy, fx, fy, rax, ray, rbx, rby;
+                  S::point_impulses(rc, hit1, ima, iia, imb, iib, vax, vay, wa, vbx, vby, wb, jx, jy, fx, fy, rax, ray,
+                                    rbx, rby);
+                  stage_point((bj >> (hit1 ? 24 : 8)) & 0xff, rc.ab, jx, jy, fx, fy, rax, ray, rbx, rby);
+                  if (hit1) { rp[15 + 8] = rc.lam_n[1]; rp[15 + 9] = rc.lam_t[1]; }
+                  else { rp[5 + 8] = rc.lam_n[0]; rp[5 + 9] = rc.lam_t[0]; }
+                }
+              };
+              for (int lv = 0; lv < wave_clevels; ++lv) {
+                const int c = cnt_of(lv);
+                for (int base = 0; __any(base < c); base += G) {
+                  if (base + k < c) {
+                    const int q = (int)sched[lv * K::LCAP + base + k] - K::NREG;
+                    if (q < K::POOL) listed_points(to_lds(pool + q * kRecW));
+                    else listed_points(spill + (q - K::POOL) * kRecW);
+                  }
+                }
+              }
+            }
+            pm = group_or(pm);
+            wave_sync();
+            if (__any(pm != 0u)) {
+              if (movable && pm != 0u) {
+                float vx = E[L.vel_x + k], vy = E[L.vel_y + k], w = E[L.omega + k];
+                const float im = E[L.inv_mass + k], ii = E[L.inv_inertia + k];
+                for (unsigned m = pm; m != 0u; m &= m - 1u) {
+                  LdsCF p = (LdsCF)(E + K::X_STAGE + (__ffs(m) - 1) * K::kManW);
+                  const int ab = f2i(p[8]);
+                  if ((ab & 0xff) == k) {
+                    apply_impulse(vx, vy, w, im, ii, p[0], p[1], p[4], p[5]);
+                    apply_impulse(vx, vy, w, im, ii, p[2], p[3], p[4], p[5]);
+                  } else if ((ab >> 8) == k) {
+                    apply_impulse(vx, vy, w, im, ii, -p[0], -p[1], p[6], p[7]);
+                    apply_impulse(vx, vy, w, im, ii, -p[2], -p[3], p[6], p[7]);
+                  }
+                }
+                E[L.vel_x + k] = vx; E[L.vel_y + k] = vy; E[L.omega + k] = w;
+              }
+              wave_sync();
+            }
+          }
+        } else
         for_each_level([&](typename S::Own& o) { S::template visit_own<false>(E, o); },
                        [&](int q) {
                          // (the two branches keep LDS and HBM accesses apart: a merged pointer would turn
@@ -1576,13 +1733,13 @@ int caps_class(const k2d_caps* c) {
 }
 int rec_words_of(int cls) { return cls == 0 ? CfgS::REC_WORDS : cls == 1 ? CfgM::REC_WORDS : CfgL::REC_WORDS; }
 
-template <class K, bool RESET>
+template <class K, bool RESET, bool BATCHED>
 int launch_step(float* state, const float* actions, int n_envs, int n_steps, const Params& prm, const float* levels,
                 int n_levels, const int32_t* reset_level, int32_t* order, int rec_words, const k2d_layout& layout,
                 hipStream_t st) {
   static bool attr_done = false;
   if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k2d_step_kernel<K, RESET>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k2d_step_kernel<K, RESET, BATCHED>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, K::LDS_BYTES) != hipSuccess)
       return K2D_E_HIP;
     attr_done = true;
@@ -1594,7 +1751,7 @@ int launch_step(float* state, const float* actions, int n_envs, int n_steps, con
                        layout);
     hipLaunchKernelGGL(k2d_order_kernel, dim3(1), dim3(1024), 0, st, keys, order, n_envs, grid * K::EPW);
   }
-  hipLaunchKernelGGL((k2d_step_kernel<K, RESET>), dim3(grid), dim3(64), K::LDS_BYTES, st, state, actions, n_envs,
+  hipLaunchKernelGGL((k2d_step_kernel<K, RESET, BATCHED>), dim3(grid), dim3(64), K::LDS_BYTES, st, state, actions, n_envs,
                      n_steps, prm, levels, n_levels, reset_level, order);
   return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
 }
@@ -1629,19 +1786,31 @@ static Params device_params(const k2d_params& p) {
   prm.rest_thr = p.restitution_threshold;
   prm.clip_thr = p.clip_thruster_01;
   prm.joint_alpha = p.joint_alpha; prm.joint_beta = p.joint_beta; prm.tie_eps = p.tie_eps;
+  prm.n_batches = 0;
   return prm;
 }
 
+template <bool RESET, bool BATCHED>
+static int step_launch_as(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, const float* lv, int n_levels,
+                          const int32_t* reset_level_dev, hipStream_t st) {
+  Params prm = device_params(b->params);
+  if (BATCHED) {
+    prm.n_batches = (2 * b->layout.n_pairs + b->params.batch_size - 1) / b->params.batch_size;
+    if (prm.n_batches < 2) return K2D_E_ARG;   // (the kernel relies on the two points of a pair being in different batches)
+  }
+  int32_t* ord = n_steps >= kOrderMinSteps ? b->order : nullptr;
+  switch (b->cls) {
+    case 0: return launch_step<CfgS, RESET, BATCHED>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
+    case 1: return launch_step<CfgM, RESET, BATCHED>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
+    default: return launch_step<CfgL, RESET, BATCHED>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
+  }
+}
 template <bool RESET>
 static int step_launch(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, const float* lv, int n_levels,
                        const int32_t* reset_level_dev, hipStream_t st) {
-  const Params prm = device_params(b->params);
-  int32_t* ord = n_steps >= kOrderMinSteps ? b->order : nullptr;
-  switch (b->cls) {
-    case 0: return launch_step<CfgS, RESET>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
-    case 1: return launch_step<CfgM, RESET>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
-    default: return launch_step<CfgL, RESET>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
-  }
+  if (b->params.batch_size > 0)
+    return step_launch_as<RESET, true>(b, actions_dev, n_envs, n_steps, lv, n_levels, reset_level_dev, st);
+  return step_launch_as<RESET, false>(b, actions_dev, n_envs, n_steps, lv, n_levels, reset_level_dev, st);
 }
 
 extern "C" {
@@ -1666,6 +1835,7 @@ int k2d_alloc_batch(const k2d_caps* caps, const k2d_params* params, int n_envs, 
   int cls = caps_class(caps);
   if (cls < 0) return K2D_E_CAP;
   if (params->n_substeps < 1 || params->n_iters < 0 || !(params->dt > 0.f)) return K2D_E_ARG;
+  if (params->batch_size < 0 || params->batch_size > K2D_MAX_BATCH_SIZE) return K2D_E_ARG;
   if (state_bytes < k2d_state_bytes(caps, n_envs)) return K2D_E_SIZE;
   k2d_batch* b = new (std::nothrow) k2d_batch;
   if (!b) return K2D_E_ARG;

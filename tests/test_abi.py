@@ -55,6 +55,9 @@ def test_argument_errors_without_device_work():
     assert lib.k2d_alloc_batch(ctypes.byref(caps), ctypes.byref(prm), 4, fake, 16, ctypes.byref(h)) == -3
     assert lib.k2d_alloc_batch(ctypes.byref(caps), ctypes.byref(prm), 4, ctypes.c_void_p(0x1000101), 1 << 20,
                                ctypes.byref(h)) == -1
+    for bad_b in (-1, 33):                                                        # batches of 0 (off) .. 32 points
+        prm_b = binding.make_params(dict(scenegen.default_params(), batch_size=bad_b))
+        assert lib.k2d_alloc_batch(ctypes.byref(caps), ctypes.byref(prm_b), 4, fake, 1 << 20, ctypes.byref(h)) == -1
     assert lib.k2d_alloc_batch(ctypes.byref(caps), ctypes.byref(prm), 4, fake, 1 << 20, ctypes.byref(h)) == 0
     assert lib.k2d_step(h, None, 4, 1, None) == -1
     assert lib.k2d_step(h, fake, 5, 1, None) == -3

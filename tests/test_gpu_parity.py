@@ -76,6 +76,51 @@ def test_stacking_workload_bit_identical():
     assert ((os_["pair_count"] > 0).sum(1) == 13).all()
 
 
+@pytest.mark.parametrize("cfg,B,n,steps", [(0, 16, 67, 120), (0, 1, 67, 60), (0, 32, 131, 60), (1, 16, 131, 64),
+                                           (1, 5, 67, 48), (2, 16, 259, 64), (2, 1, 131, 32), (2, 32, 131, 48),
+                                           (3, 16, 131, 64), (3, 7, 67, 48), (4, 16, 195, 48)])
+def test_batched_schedule_bit_identical(cfg, B, n, steps):
+    """The batched impulse resolution of A.8 (16 is the paper's batch size; 1 is the sequential sweep, 32 the
+    largest the library takes), odd and even numbers of shapes, against the oracle running the same schedule."""
+    caps, prm, sc = scenegen.make_scene(cfg, n_envs=n)
+    prm = dict(prm, batch_size=B)
+    act = scenegen.make_actions(cfg, steps, n)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b = parity.run_gpu(caps, prm, sc, act)
+    gs, os_ = b.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    assert (os_["pair_count"] > 0).sum() > n
+    if B == 1:      # and that is the default schedule's result
+        b0 = parity.run_gpu(caps, dict(prm, batch_size=0), sc, act)
+        assert np.array_equal(b0.read_state().cpu().numpy(), b.read_state().cpu().numpy())
+
+
+def test_batched_schedule_on_the_towers_and_with_restarts():
+    import torch
+    import paper_2410_23208_amd as k2d
+    caps, prm, sc = scenegen.make_stack_scene(n_envs=131)
+    prm = dict(prm, batch_size=16)
+    act = np.zeros((96, 131, caps[2] + caps[3]), dtype=np.float32)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b = parity.run_gpu(caps, prm, sc, act)
+    gs, os_ = b.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    assert ((os_["pair_count"] > 0).sum(1) == 13).all()
+    # the launch that restarts episodes runs the same schedule: no restarts scheduled == plain launch
+    caps, prm, sc = scenegen.make_scene(2, n_envs=67)
+    prm = dict(prm, batch_size=16)
+    act = torch.from_numpy(scenegen.make_actions(2, 24, 67)).cuda()
+    words = k2d.pack_scenes(caps, sc)
+    x, y = k2d.Batch(caps, 67, prm), k2d.Batch(caps, 67, prm)
+    x.reset(words)
+    y.reset(words)
+    x.step(act)
+    y.step_reset(act, torch.from_numpy(words.view(np.int32)).cuda(), torch.full((24, 67), -1, dtype=torch.int32).cuda())
+    assert np.array_equal(x.read_state().cpu().numpy(), y.read_state().cpu().numpy())
+
+
 def test_contacts_and_observation_outputs():
     b, o, caps = _both(3, 131, 40)
     pc, adj = b.read_contacts()
@@ -283,9 +328,10 @@ def test_single_environment_and_empty_scene():
     assert os_["pair_count"].sum() >= 2
 
 
-def test_pile_deeper_than_the_lds_pool():
+@pytest.mark.parametrize("B", [0, 16, 32, 3])
+def test_pile_deeper_than_the_lds_pool(B):
     """All 16 shapes of an L scene dumped onto one spot: far more active pairs than the per-environment
-    LDS pool holds, so the overflow path through the HBM record is exercised."""
+    LDS pool holds, so the overflow path through the HBM record is exercised (under both schedules)."""
     caps = scenegen.CAPS["L"]
     sb = SceneBuilder(caps, n_envs=3)
     rng = np.random.default_rng(5)
@@ -295,7 +341,7 @@ def test_pile_deeper_than_the_lds_pool():
             sb.box(0.3 + 0.02 * k, 0.25, (0.05 * k + 0.01 * e, 0.5 + 0.04 * k), theta=0.1 * k, friction=0.4, e=e)
         for k in range(4):
             sb.circle(0.3, (0.1 * k, 0.6 + 0.05 * k), e=e)
-    prm = mkparams(n_substeps=3, n_iters=10, alpha=0.5, beta=0.02)   # gentle corrections: the pile persists
+    prm = mkparams(n_substeps=3, n_iters=10, alpha=0.5, beta=0.02, batch_size=B)   # gentle corrections: the pile persists
     sc = sb.scene()
     act = np.zeros((6, 3, caps[2] + caps[3]), dtype=np.float32)
     o = parity.run_oracle(caps, prm, sc, act)
