@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=2, help="workload 0..4 (default 2 = L, 8192 envs x 256 steps)")
     ap.add_argument("--cpu-envs", type=int, default=8192, help="environments of the CPU-oracle sample")
+    ap.add_argument("--batch-size", type=int, default=0, help="0 = the default schedule (dependency levels, the "
+                    "sequential sweep's bits); 1..32 = the batched impulse resolution of A.8 with that batch size")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain 256 MiB device copy, so "
                     "that a counter run has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg (flop model then uses "
@@ -64,6 +66,7 @@ def main():
     cfg = scenegen.CONFIGS[args.config]
     n_envs, n_steps = cfg["n_envs"], cfg["n_steps"]
     caps, params, scene = scenegen.make_scene(args.config)
+    params = dict(params, batch_size=args.batch_size)
     actions_h = scenegen.make_actions(args.config, n_steps, n_envs)
     dev = torch.device("cuda:0")
     words = torch.from_numpy(k2d.pack_scenes(caps, scene).view(np.int32)).to(dev)
@@ -151,9 +154,10 @@ def main():
         "config": {"workload": "config %d: %s, %d envs x %d steps, %d substeps x %d solver sweeps, caps P/C/J/T=%s"
                    % (args.config, cfg["name"], n_envs, n_steps, params["n_substeps"], params["n_iters"],
                       "/".join(map(str, caps))),
-                   "env_steps_per_launch": env_steps, "seed": scenegen.SEED},
+                   "env_steps_per_launch": env_steps, "seed": scenegen.SEED,
+                   "schedule": "dependency levels" if args.batch_size == 0 else "batches of %d (A.8)" % args.batch_size},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / FP32_VALU_PEAK_TFLOPS, "traffic": read_traffic(cfg["name"]),
+                     "frac": achieved / FP32_VALU_PEAK_TFLOPS, "traffic": read_traffic(cfg["name"]) if args.batch_size == 0 else None,
                      "kernel": "k2d_step_kernel", "kernel_ms_avg": kern_avg * 1e3, "kernel_ms": kern_ms,
                      "flops_per_env_step": flops_step, "active_points_per_substep": float(slots),
                      "active_pairs_per_substep": float(pairs), "eligible_pairs": st["n_eligible"],
