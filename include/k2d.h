@@ -190,6 +190,13 @@ typedef struct {
 int k2d_read_outcome(k2d_batch* batch, const k2d_reward_params* params, float* dist_dev, float* reward_dev,
                      uint8_t* done_dev, void* stream);
 
+/* Health check of the batch (a solver of this kind can blow up: A.8 names the stability cost of parallel
+ * constraint solving): bad_dev[e] = 1 if position, rotation or velocity of an active shape of environment e
+ * is infinite or NaN, else 0; *count_dev = number of such environments.  bad_dev: device, n_envs bytes;
+ * count_dev: device, one int32 (overwritten).  Enqueued on `stream`; the caller owns both buffers.
+ * K2D_E_ARG on a null pointer. */
+int k2d_read_health(k2d_batch* batch, uint8_t* bad_dev, int32_t* count_dev, void* stream);
+
 /* Copies full records ([n_envs][state_words] words, layout above) out of / into the batch
  * (checkpoint and resume; k2d_write_state keeps the accumulators it is given). */
 int k2d_read_state(k2d_batch* batch, void* records_dev, void* stream);

@@ -159,3 +159,11 @@ def entities(flat_obs, scene, shape_adj, caps):
             masks[e, 2, i] = reach[i]
             masks[e, 3, i] = int(shape_adj[e, i])
     return dict(shapes=shapes, joints=joints, joint_idx=jidx, thrusters=thr, thruster_idx=tidx, masks=masks)
+
+
+def health(pos, theta, vel, omega, active):
+    """Which environments have blown up: position (n, N, 2), rotation (n, N), velocity (n, N, 2) or angular
+    velocity (n, N) of an active shape (active: n, N) is infinite or NaN.  Returns (bad uint8 [n], count)."""
+    finite = (np.isfinite(pos).all(-1) & np.isfinite(theta) & np.isfinite(vel).all(-1) & np.isfinite(omega))
+    bad = ((~finite) & (np.asarray(active) != 0)).any(-1)
+    return bad.astype(np.uint8), int(bad.sum())

@@ -70,6 +70,7 @@ def lib():
         L.k2d_read_entities.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
         L.k2d_decode_actions.argtypes = [ctypes.POINTER(k2d_caps), vp, vp, ctypes.c_size_t, vp]
         L.k2d_read_outcome.argtypes = [vp, ctypes.POINTER(k2d_reward_params), vp, vp, vp, vp]
+        L.k2d_read_health.argtypes = [vp, vp, vp, vp]
         L.k2d_read_state.argtypes = [vp, vp, vp]
         L.k2d_write_state.argtypes = [vp, vp, vp]
         _lib = L
@@ -78,7 +79,7 @@ def lib():
 
 EXPORTS = ["k2d_get_layout", "k2d_state_bytes", "k2d_alloc_batch", "k2d_free_batch", "k2d_reset", "k2d_step",
            "k2d_step_reset", "k2d_read_outcome", "k2d_read_entities", "k2d_decode_actions",
-           "k2d_read_obs", "k2d_read_contacts", "k2d_read_state", "k2d_write_state"]
+           "k2d_read_obs", "k2d_read_contacts", "k2d_read_health", "k2d_read_state", "k2d_write_state"]
 
 
 def _check(rc, what):
@@ -306,6 +307,14 @@ class Batch:
         _check(lib().k2d_read_outcome(self._h, ctypes.byref(rp), dist.data_ptr(), reward.data_ptr(), done.data_ptr(),
                                       self._stream()), "k2d_read_outcome")
         return reward, done
+
+    def read_health(self):
+        """(bad uint8 [n_envs], count int32 [1]): environments whose active shapes hold a non-finite value."""
+        torch = self.torch
+        bad = torch.empty(self.n_envs, dtype=torch.uint8, device=self.device)
+        count = torch.empty(1, dtype=torch.int32, device=self.device)
+        _check(lib().k2d_read_health(self._h, bad.data_ptr(), count.data_ptr(), self._stream()), "k2d_read_health")
+        return bad, count
 
     def read_contacts(self):
         torch = self.torch

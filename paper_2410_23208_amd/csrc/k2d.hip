@@ -1712,6 +1712,30 @@ __global__ void __launch_bounds__(64) k2d_outcome_kernel(const float* state, flo
   }
 }
 
+// Health of the batch: an environment is flagged when position, rotation or velocity of one of its active
+// shapes is not finite (a simulation that blew up).  16 lanes per environment, lane i looks at shape i.
+__global__ void k2d_zero_word_kernel(int32_t* w) { *w = 0; }
+__global__ void __launch_bounds__(64) k2d_health_kernel(const float* state, uint8_t* bad, int32_t* count, int n_envs,
+                                                        int rec_words, k2d_layout L) {
+  const int lane = threadIdx.x, i = lane & 15;
+  const int env = blockIdx.x * 4 + (lane >> 4);
+  const bool ok = env < n_envs;
+  const float* S = state + (size_t)(ok ? env : 0) * rec_words;
+  int mine = 0;
+  if (ok && i < L.n_shapes && (__float_as_int(S[L.shape_flags + i]) & 1)) {
+    const int words[6] = {L.pos_x, L.pos_y, L.theta, L.vel_x, L.vel_y, L.omega};
+    for (int w = 0; w < 6; ++w) {
+      const unsigned u = (unsigned)__float_as_int(S[words[w] + i]);
+      if ((u & 0x7f800000u) == 0x7f800000u) mine = 1;   // exponent all ones: infinity or NaN
+    }
+  }
+  for (int d = 8; d >= 1; d >>= 1) mine |= __shfl_xor(mine, d, 16);
+  if (ok && i == 0) {
+    bad[env] = (uint8_t)mine;
+    if (mine) atomicAdd(count, 1);
+  }
+}
+
 // ---------------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------------
@@ -1932,6 +1956,16 @@ int k2d_read_outcome(k2d_batch* b, const k2d_reward_params* rp, float* dist_dev,
   hipLaunchKernelGGL(k2d_outcome_kernel, dim3((b->n_envs + 3) / 4), dim3(64), 0, static_cast<hipStream_t>(stream),
                      b->state, dist_dev, reward_dev, done_dev, b->n_envs, b->rec_words, b->layout, rp->kappa,
                      rp->role_green, rp->role_blue, rp->role_red);
+  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+}
+
+int k2d_read_health(k2d_batch* b, uint8_t* bad_dev, int32_t* count_dev, void* stream) {
+  if (!b || !bad_dev || !count_dev) return K2D_E_ARG;
+  if (b->layout.n_shapes > 16) return K2D_E_CAP;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(k2d_zero_word_kernel, dim3(1), dim3(1), 0, st, count_dev);
+  hipLaunchKernelGGL(k2d_health_kernel, dim3((b->n_envs + 3) / 4), dim3(64), 0, st, b->state, bad_dev, count_dev,
+                     b->n_envs, b->rec_words, b->layout);
   return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
 }
 

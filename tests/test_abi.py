@@ -72,6 +72,8 @@ def test_argument_errors_without_device_work():
     rp = binding.k2d_reward_params(1.0, 1, 2, 3)
     assert lib.k2d_read_outcome(h, None, fake, fake, fake, None) == -1
     assert lib.k2d_read_outcome(h, ctypes.byref(rp), None, fake, fake, None) == -1
+    assert lib.k2d_read_health(h, None, fake, None) == -1
+    assert lib.k2d_read_health(h, fake, None, None) == -1
     assert lib.k2d_free_batch(h) == 0
 
 

@@ -446,3 +446,31 @@ def test_long_rollout_statistics():
     ho = np.bincount((os_["pair_count"] > 0).sum(1).astype(int), minlength=40)
     assert np.abs(hg - ho).sum() <= 0.02 * len(gs["pos"])
     assert not np.isnan(gs["pos"]).any()
+
+
+def test_health_check_flags_the_environments_with_non_finite_state():
+    """k2d_read_health against the numpy definition: values planted through k2d_write_state (NaN, infinities,
+    in active and in inactive shapes), and a clean batch."""
+    import torch
+    import paper_2410_23208_amd as k2d
+    from oracle import k2d_env
+    caps, prm, sc = scenegen.make_scene(1, n_envs=133)      # M scenes: some shapes inactive
+    b = k2d.Batch(caps, 133, prm)
+    b.reset(k2d.pack_scenes(caps, sc))
+    b.step(torch.from_numpy(scenegen.make_actions(1, 8, 133)).cuda())
+    bad, count = b.read_health()
+    assert int(count.item()) == 0 and not bad.any().item()
+    L = k2d.get_layout(caps)
+    rec = b.read_state().cpu().numpy().view(np.float32).copy()
+    rng = np.random.default_rng(11)
+    N = L["n_shapes"]
+    for e in rng.choice(133, size=40, replace=False):
+        field = ["pos_x", "pos_y", "theta", "vel_x", "vel_y", "omega"][int(rng.integers(6))]
+        rec[e, L[field] + int(rng.integers(N))] = [np.nan, np.inf, -np.inf][int(rng.integers(3))]
+    b.write_state(torch.from_numpy(rec.view(np.int32)).cuda())
+    st = k2d.unpack_state(caps, rec.view(np.uint32))
+    want, n_want = k2d_env.health(st["pos"].reshape(133, N, 2), st["theta"], st["vel"].reshape(133, N, 2),
+                                  st["omega"], st["active"])
+    bad, count = b.read_health()
+    assert np.array_equal(bad.cpu().numpy(), want) and int(count.item()) == n_want
+    assert 0 < n_want < 40                                  # some of the planted values sit in inactive shapes

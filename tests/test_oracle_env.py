@@ -151,3 +151,19 @@ def test_observation_widths_match_the_papers_tables():
         per_poly = width["shape"] - sym["n_roles"] - sym["n_types"] - 1 - 2 + 1 + 1 + 1   # no radius, n_verts, active, role
         per_circ = width["shape"] - sym["n_roles"] - sym["n_types"] - 8 - 2 + 1 + 1        # no vertices, active, role
         assert o.obs().shape[1] == P * per_poly + C * per_circ + J * width["joint"] + T * width["thruster"]
+
+
+# ------------------------------------------------------------------ health of the batch
+def test_health_flags_non_finite_active_shapes_only():
+    n, N = 6, 4
+    pos, vel = np.zeros((n, N, 2)), np.ones((n, N, 2))
+    theta, omega = np.zeros((n, N)), np.zeros((n, N))
+    active = np.ones((n, N), dtype=np.int64)
+    active[:, 3] = 0
+    pos[1, 0, 1] = np.nan           # active shape: flagged
+    vel[2, 2, 0] = -np.inf          # active shape: flagged
+    omega[3, 3] = np.nan            # inactive shape: ignored
+    theta[4, 1] = np.inf            # active: flagged
+    vel[5, 0] = 3.0e38              # huge but finite: fine
+    bad, count = k2d_env.health(pos, theta, vel, omega, active)
+    assert bad.tolist() == [0, 1, 1, 0, 1, 0] and count == 3
