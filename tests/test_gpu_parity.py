@@ -435,6 +435,27 @@ def test_full_size_launch_sampled_against_oracle(cfg, steps, n_sample):
     assert np.array_equal(full["pos"][static], np.asarray(sc["pos"]).reshape(n, -1)[static])
 
 
+def test_very_many_environments_sampled_against_oracle():
+    """300 000 small environments in one launch (record and action offsets beyond 2^31 bytes are not reached
+    here, beyond 2^27 words are): a seeded sample, the first and the last environment against the oracle."""
+    import torch
+    import paper_2410_23208_amd as k2d
+    n, steps = 300000, 12
+    caps, prm, sc = scenegen.make_scene(0, n_envs=n)
+    act = scenegen.make_actions(0, steps, n)
+    b = k2d.Batch(caps, n, prm)
+    b.reset(k2d.pack_scenes(caps, sc))
+    b.step(torch.from_numpy(act).cuda(), steps)
+    ids = np.sort(np.random.default_rng(3).choice(n, size=96, replace=False))
+    ids[0], ids[-1] = 0, n - 1
+    gs = k2d.unpack_state(caps, b.read_state()[torch.from_numpy(ids).cuda()].cpu().numpy())
+    os_ = parity.run_oracle(caps, prm, scenegen.select_envs(sc, ids), act[:, ids]).state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    bad, count = b.read_health()
+    assert int(count.item()) == 0
+
+
 def test_long_rollout_statistics():
     """Beyond the element-wise horizon: distribution statistics of a 256-step rollout agree."""
     b, o, caps = _both(2, 515, 256)
