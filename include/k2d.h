@@ -123,7 +123,8 @@ int k2d_reset(k2d_batch* batch, const void* scenes_dev, const int32_t* env_ids_d
 /* Advances every environment by n_steps steps of the engine's main loop (Algorithm 1: gravity, collision
  * manifolds of all shape pairs (A.3.1-A.3.4), motors (A.5), thrusters (A.6), warm starting (A.7), n_iters
  * sweeps of joint (A.4) then collision (A.3.5-A.3.7) constraints, Euler step, positional corrections),
- * each step being n_substeps passes with the same action.
+ * each step being n_substeps passes with the same action.  The collision constraints of a sweep run in the
+ * schedule that k2d_params.batch_size selects (A.8).
  * actions_dev: float [n_steps][n_envs][J+T]: first the J motor actions, then the T thruster actions.
  * n_envs must equal the batch's. */
 int k2d_step(k2d_batch* batch, const float* actions_dev, int n_envs, int n_steps, void* stream);
