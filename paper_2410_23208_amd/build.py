@@ -14,19 +14,37 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
          "-fPIC", "-shared", "-I" + os.path.join(ROOT, "include")]
 
 
+HEADER = os.path.join(ROOT, "include", "k2d.h")
+
+
 def build(verbose=False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + FLAGS + ["-o", LIB, SRC]
     if verbose:
         print(" ".join(cmd))
-    subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL if not verbose else None,
-                   stderr=subprocess.DEVNULL if not verbose else None)
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed (exit %d):\n%s\n%s" % (r.returncode, r.stdout[-4000:], r.stderr[-8000:]))
+    if verbose:
+        print(r.stderr)
     return LIB
 
 
-def ensure_built():
-    """Path of the built library; builds it only if it is missing."""
+def stale():
+    """True if the library is missing or older than its source or the header."""
     if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.exists(f) and os.path.getmtime(f) > t for f in (SRC, HEADER))
+
+
+def ensure_built():
+    """Path of the built library; rebuilds it when it is missing or older than k2d.hip / k2d.h (where no
+    compiler is installed, a library that is there is used as it is)."""
+    if stale():
+        hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+        if os.path.exists(LIB) and not os.path.exists(hipcc):
+            return LIB
         build()
     return LIB
 
