@@ -129,6 +129,19 @@ int k2d_reset(k2d_batch* batch, const void* scenes_dev, const int32_t* env_ids_d
  * n_envs must equal the batch's. */
 int k2d_step(k2d_batch* batch, const float* actions_dev, int n_envs, int n_steps, void* stream);
 
+/* k2d_step for callers that cannot allocate device memory or size a workspace for the library: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs and
+ * results as k2d_step; the one difference is where the launch keeps its ordering of the environments (the
+ * eight bytes per environment that k2d_step takes from the tail of the caller's state buffer): here it is
+ * a fixed array inside the library's code object, one copy per GPU, 2 * K2D_NOALLOC_MAX_ENVS * 4 bytes,
+ * held until the process ends.  Calls hipMalloc / hipFree or any allocating routine never; the array's
+ * device address is looked up once per device (k2d_alloc_batch does it when a device is current, else the
+ * first call here).  K2D_E_SIZE if n_envs > K2D_NOALLOC_MAX_ENVS.  All calls on one GPU share that GPU's
+ * array: calls that may overlap in time on one GPU (different streams) race on it and must be ordered by
+ * the caller; every call rewrites the part it uses, nothing has to be cleared between calls. */
+#define K2D_NOALLOC_MAX_ENVS 65536
+int k2d_step_noalloc(k2d_batch* batch, const float* actions_dev, int n_envs, int n_steps, void* stream);
+
 /* k2d_step with new episodes started inside the launch (training runs every environment on levels sampled
  * anew whenever an episode ends, Sec. 4; Appendix B times the engine over whole rollouts): after step s
  * (0-based) every environment e with reset_level_dev[s * n_envs + e] = l, 0 <= l < n_levels, is

@@ -64,6 +64,7 @@ def lib():
         L.k2d_free_batch.argtypes = [vp]
         L.k2d_reset.argtypes = [vp, vp, vp, i32, vp]
         L.k2d_step.argtypes = [vp, vp, i32, i32, vp]
+        L.k2d_step_noalloc.argtypes = [vp, vp, i32, i32, vp]
         L.k2d_step_reset.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp]
         L.k2d_read_obs.argtypes = [vp, vp, vp]
         L.k2d_read_contacts.argtypes = [vp, vp, vp, vp]
@@ -78,7 +79,7 @@ def lib():
 
 
 EXPORTS = ["k2d_get_layout", "k2d_state_bytes", "k2d_alloc_batch", "k2d_free_batch", "k2d_reset", "k2d_step",
-           "k2d_step_reset", "k2d_read_outcome", "k2d_read_entities", "k2d_decode_actions",
+           "k2d_step_noalloc", "k2d_step_reset", "k2d_read_outcome", "k2d_read_entities", "k2d_decode_actions",
            "k2d_read_obs", "k2d_read_contacts", "k2d_read_health", "k2d_read_state", "k2d_write_state"]
 
 
@@ -248,6 +249,15 @@ class Batch:
         assert actions.is_cuda and actions.dtype == self.torch.float32 and actions.is_contiguous()
         assert actions.numel() >= n_steps * self.n_envs * (self.J + self.T)
         _check(lib().k2d_step(self._h, actions.data_ptr(), self.n_envs, int(n_steps), self._stream()), "k2d_step")
+
+    def step_noalloc(self, actions, n_steps=None):
+        """k2d_step_noalloc: the same step, with the launch's ordering scratch inside the library."""
+        if n_steps is None:
+            n_steps = actions.shape[0]
+        assert actions.is_cuda and actions.dtype == self.torch.float32 and actions.is_contiguous()
+        assert actions.numel() >= n_steps * self.n_envs * (self.J + self.T)
+        _check(lib().k2d_step_noalloc(self._h, actions.data_ptr(), self.n_envs, int(n_steps), self._stream()),
+               "k2d_step_noalloc")
 
     def step_reset(self, actions, levels, reset_level, n_steps=None):
         """k2d_step with episodes restarted inside the launch.  levels: device int32/float32 words

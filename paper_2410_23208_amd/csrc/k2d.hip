@@ -35,6 +35,7 @@
 
 #include <cstdint>
 #include <cstdlib>
+#include <mutex>
 #include <new>
 
 #include "k2d.h"
@@ -1757,16 +1758,46 @@ int caps_class(const k2d_caps* c) {
 }
 int rec_words_of(int cls) { return cls == 0 ? CfgS::REC_WORDS : cls == 1 ? CfgM::REC_WORDS : CfgL::REC_WORDS; }
 
+// Per-device host bookkeeping (a process may drive several GPUs from several threads).
+constexpr int kMaxDevices = 64;
+std::mutex g_host_mutex;
+
+// Ordering scratch of k2d_step_noalloc: slot -> environment for one launch, then the sort keys.  One copy
+// per GPU, inside the code object, held until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; kernels get the address that call returns.
+constexpr int kNoAllocSlots = (K2D_NOALLOC_MAX_ENVS + 3) / 4 * 4;
+__device__ __align__(256) int32_t scratch[2 * kNoAllocSlots];
+int32_t* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of `scratch` (looked up once per device).
+int scratch_of_current_device(int32_t** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return K2D_E_HIP;
+  std::lock_guard<std::mutex> lock(g_host_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return K2D_E_HIP;
+    g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return K2D_OK;
+}
+
 template <class K, bool RESET, bool BATCHED>
 int launch_step(float* state, const float* actions, int n_envs, int n_steps, const Params& prm, const float* levels,
                 int n_levels, const int32_t* reset_level, int32_t* order, int rec_words, const k2d_layout& layout,
                 hipStream_t st) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k2d_step_kernel<K, RESET, BATCHED>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, K::LDS_BYTES) != hipSuccess)
-      return K2D_E_HIP;
-    attr_done = true;
+  {   // the kernel's LDS image is larger than the default limit: raise it once per device
+    static bool attr_done[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return K2D_E_HIP;
+    std::lock_guard<std::mutex> lock(g_host_mutex);
+    if (!attr_done[dev]) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k2d_step_kernel<K, RESET, BATCHED>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, K::LDS_BYTES) != hipSuccess)
+        return K2D_E_HIP;
+      attr_done[dev] = true;
+    }
   }
   int grid = (n_envs + K::EPW - 1) / K::EPW;
   if (order) {   // (a launch of a few steps is not worth the ordering pass)
@@ -1816,13 +1847,13 @@ static Params device_params(const k2d_params& p) {
 
 template <bool RESET, bool BATCHED>
 static int step_launch_as(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, const float* lv, int n_levels,
-                          const int32_t* reset_level_dev, hipStream_t st) {
+                          const int32_t* reset_level_dev, int32_t* order_buf, hipStream_t st) {
   Params prm = device_params(b->params);
   if (BATCHED) {
     prm.n_batches = (2 * b->layout.n_pairs + b->params.batch_size - 1) / b->params.batch_size;
     if (prm.n_batches < 2) return K2D_E_ARG;   // (the kernel relies on the two points of a pair being in different batches)
   }
-  int32_t* ord = n_steps >= kOrderMinSteps ? b->order : nullptr;
+  int32_t* ord = n_steps >= kOrderMinSteps ? order_buf : nullptr;
   switch (b->cls) {
     case 0: return launch_step<CfgS, RESET, BATCHED>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
     case 1: return launch_step<CfgM, RESET, BATCHED>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
@@ -1831,10 +1862,10 @@ static int step_launch_as(k2d_batch* b, const float* actions_dev, int n_envs, in
 }
 template <bool RESET>
 static int step_launch(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, const float* lv, int n_levels,
-                       const int32_t* reset_level_dev, hipStream_t st) {
+                       const int32_t* reset_level_dev, int32_t* order_buf, hipStream_t st) {
   if (b->params.batch_size > 0)
-    return step_launch_as<RESET, true>(b, actions_dev, n_envs, n_steps, lv, n_levels, reset_level_dev, st);
-  return step_launch_as<RESET, false>(b, actions_dev, n_envs, n_steps, lv, n_levels, reset_level_dev, st);
+    return step_launch_as<RESET, true>(b, actions_dev, n_envs, n_steps, lv, n_levels, reset_level_dev, order_buf, st);
+  return step_launch_as<RESET, false>(b, actions_dev, n_envs, n_steps, lv, n_levels, reset_level_dev, order_buf, st);
 }
 
 extern "C" {
@@ -1871,6 +1902,10 @@ int k2d_alloc_batch(const k2d_caps* caps, const k2d_params* params, int n_envs, 
   b->rec_words = rec_words_of(cls);
   b->state = static_cast<float*>(state_dev);
   b->order = reinterpret_cast<int32_t*>(static_cast<char*>(state_dev) + records_bytes(cls, n_envs));
+  {   // set-up for k2d_step_noalloc on this device (nothing to do, and no error, where no GPU is visible)
+    int32_t* unused = nullptr;
+    (void)scratch_of_current_device(&unused);
+  }
   *out = b;
   return K2D_OK;
 }
@@ -1891,7 +1926,18 @@ int k2d_reset(k2d_batch* b, const void* scenes_dev, const int32_t* env_ids_dev, 
 int k2d_step(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, void* stream) {
   if (!b || !actions_dev || n_steps < 1) return K2D_E_ARG;
   if (n_envs != b->n_envs) return K2D_E_SIZE;
-  return step_launch<false>(b, actions_dev, n_envs, n_steps, nullptr, 0, nullptr, static_cast<hipStream_t>(stream));
+  return step_launch<false>(b, actions_dev, n_envs, n_steps, nullptr, 0, nullptr, b->order,
+                            static_cast<hipStream_t>(stream));
+}
+
+int k2d_step_noalloc(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, void* stream) {
+  if (!b || !actions_dev || n_steps < 1) return K2D_E_ARG;
+  if (n_envs != b->n_envs) return K2D_E_SIZE;
+  if (n_envs > K2D_NOALLOC_MAX_ENVS) return K2D_E_SIZE;   // the built-in scratch holds no more
+  int32_t* order_buf = nullptr;
+  if (int rc = scratch_of_current_device(&order_buf)) return rc;
+  return step_launch<false>(b, actions_dev, n_envs, n_steps, nullptr, 0, nullptr, order_buf,
+                            static_cast<hipStream_t>(stream));
 }
 
 int k2d_step_reset(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, const void* levels_dev,
@@ -1899,7 +1945,7 @@ int k2d_step_reset(k2d_batch* b, const float* actions_dev, int n_envs, int n_ste
   if (!b || !actions_dev || n_steps < 1 || !levels_dev || n_levels < 1 || !reset_level_dev) return K2D_E_ARG;
   if (n_envs != b->n_envs) return K2D_E_SIZE;
   return step_launch<true>(b, actions_dev, n_envs, n_steps, static_cast<const float*>(levels_dev), n_levels,
-                           reset_level_dev, static_cast<hipStream_t>(stream));
+                           reset_level_dev, b->order, static_cast<hipStream_t>(stream));
 }
 
 int k2d_read_obs(k2d_batch* b, float* obs_dev, void* stream) {

@@ -74,7 +74,16 @@ def test_argument_errors_without_device_work():
     assert lib.k2d_read_outcome(h, ctypes.byref(rp), None, fake, fake, None) == -1
     assert lib.k2d_read_health(h, None, fake, None) == -1
     assert lib.k2d_read_health(h, fake, None, None) == -1
+    assert lib.k2d_step_noalloc(h, None, 4, 8, None) == -1
+    assert lib.k2d_step_noalloc(h, fake, 5, 8, None) == -3
+    assert lib.k2d_step_noalloc(h, fake, 4, 0, None) == -1
     assert lib.k2d_free_batch(h) == 0
+    # the built-in scratch of k2d_step_noalloc holds K2D_NOALLOC_MAX_ENVS environments: a larger batch is refused
+    big = ctypes.c_void_p()
+    capsL = binding.make_caps((12, 4, 6, 2))
+    assert lib.k2d_alloc_batch(ctypes.byref(capsL), ctypes.byref(prm), 65537, fake, 1 << 40, ctypes.byref(big)) == 0
+    assert lib.k2d_step_noalloc(big, fake, 65537, 8, None) == -3
+    assert lib.k2d_free_batch(big) == 0
 
 
 def test_pack_unpack_roundtrip():
