@@ -115,9 +115,13 @@ int k2d_alloc_batch(const k2d_caps* caps, const k2d_params* params, int n_envs, 
 /* Frees the host descriptor only. */
 int k2d_free_batch(k2d_batch* batch);
 
-/* Starts new episodes: scenes_dev holds n records of `scene_words` words (layout above), record r goes to
- * environment env_ids_dev[r] (NULL: environment r).  Joint and contact accumulators and the pair states
- * of those environments are zeroed.  Indices out of range are skipped. */
+/* Starts new episodes (Sec. 3.1: a scene is a set of polygons, circles, joints and thrusters in
+ * fixed-capacity arrays with active masks; Table 4 gives the capacities).  scenes_dev holds n records of
+ * `scene_words` words (layout above), record r goes to environment env_ids_dev[r] (NULL: environment r).
+ * A new episode has nothing to warm-start from (A.7): the accumulated joint and collision impulses and the
+ * pair states of those environments are zeroed.  Environment indices out of range are skipped.
+ * Entities that refer to a shape index outside 0..N-1 (a joint's joint_a / joint_b, a thruster's body), and
+ * joints with joint_a == joint_b, are treated as inactive by every entry point. */
 int k2d_reset(k2d_batch* batch, const void* scenes_dev, const int32_t* env_ids_dev, int n, void* stream);
 
 /* Advances every environment by n_steps steps of the engine's main loop (Algorithm 1: gravity, collision
@@ -152,6 +156,10 @@ int k2d_step_noalloc(k2d_batch* batch, const float* actions_dev, int n_envs, int
 int k2d_step_reset(k2d_batch* batch, const float* actions_dev, int n_envs, int n_steps, const void* levels_dev,
                    int n_levels, const int32_t* reset_level_dev, void* stream);
 
+/* Floats per environment of the flat symbolic observation that k2d_read_obs writes (Tables 5-7:
+ * 23 per polygon, 15 per circle, 11 per joint, 6 per thruster); -1 on a null pointer or unsupported capacities. */
+int k2d_obs_dim(const k2d_caps* caps);
+
 /* Flat symbolic observation (the physical entries of Tables 5-7), float [n_envs][obs_dim]; per polygon:
  * pos 2, vel 2, inv_mass, inv_inertia, density, tanh(omega/10), sin theta, cos theta, friction, restitution,
  * vertices 8, n_verts, active, role (23); per circle the same 12 then radius, active, role (15); per joint:
@@ -159,9 +167,10 @@ int k2d_step_reset(k2d_batch* batch, const float* actions_dev, int n_envs, int n
  * per thruster: active, pos 2, power, sin/cos(angle) (6). */
 int k2d_read_obs(k2d_batch* batch, float* obs_dev, void* stream);
 
-/* Collisions of the last substep: pair_count_dev uint8 [n_envs][n_pairs] = active manifold points of the
- * pair (0, 1 or 2; lexicographic pair order); shape_adj_dev uint32 [n_envs][N]: bit j of word i set iff
- * shapes i and j are in active collision.  Either pointer may be NULL. */
+/* Collisions of the last substep (A.3.1, Table 2: a manifold point is an active collision iff its
+ * penetration is positive; polygon pairs have two points, A.3.4).  pair_count_dev uint8 [n_envs][n_pairs] =
+ * active manifold points of the pair (0, 1 or 2; lexicographic pair order); shape_adj_dev uint32
+ * [n_envs][N]: bit j of word i set iff shapes i and j are in active collision.  Either pointer may be NULL. */
 int k2d_read_contacts(k2d_batch* batch, uint8_t* pair_count_dev, uint32_t* shape_adj_dev, void* stream);
 
 /* Symbolic-Entity observation (Sec. 3.2 "Observation Space", Sec. 4, Appendix C Tables 5-7): the set of

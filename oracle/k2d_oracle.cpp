@@ -435,9 +435,13 @@ struct JointRow {   // fixed for one substep
   R lim_bias = 0;                // gamma * lim_excess
 };
 
+// A joint takes part only if it is active and joins two different, active shapes of which at least one can
+// move; a joint (or a thruster) that names a shape index outside the scene's arrays counts as inactive.
 template <class R>
 inline bool joint_live(const Env<R>& E, const Joint<R>& j) {
   if (!j.active) return false;
+  const int N = (int)E.bodies.size();
+  if (j.a < 0 || j.a >= N || j.b < 0 || j.b >= N) return false;
   const Body<R>& a = E.bodies[j.a];
   const Body<R>& b = E.bodies[j.b];
   return j.a != j.b && a.active && b.active && (a.inv_mass + b.inv_mass) > R(0);
@@ -684,7 +688,7 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
   // -- Apply thrusters (A.6): force p*A along the thruster direction at its mount point, held for h.
   for (int q = 0; q < nT; ++q) {
     const Thruster<R>& th = E.thrusters[q];
-    if (!th.active) continue;
+    if (!th.active || th.body < 0 || th.body >= N) continue;
     Body<R>& b = E.bodies[th.body];
     if (!b.active) continue;
     R A = R(actions[nJ + q]);
@@ -993,7 +997,9 @@ struct Batch : BatchBase {
         *o++ = b.active; *o++ = b.role;
       }
       for (const Joint<R>& j : E.joints) {
-        R rel = E.bodies[j.a].theta - E.bodies[j.b].theta;
+        // (shape indices outside the arrays -- such a joint is inactive in the step -- are clamped here)
+        const int ja = std::min(std::max(j.a, 0), N - 1), jb = std::min(std::max(j.b, 0), N - 1);
+        R rel = E.bodies[ja].theta - E.bodies[jb].theta;
         *o++ = j.active; *o++ = j.fixed;
         *o++ = j.anchor_a.x; *o++ = j.anchor_a.y; *o++ = j.anchor_b.x; *o++ = j.anchor_b.y;
         *o++ = j.motor_power; *o++ = j.motor_speed; *o++ = j.motor_on;

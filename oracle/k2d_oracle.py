@@ -28,11 +28,23 @@ OPTIONAL_FIELDS = ["joint_limited", "joint_limit_lo", "joint_limit_hi"]     # ab
 ACC_FIELDS = ["joint_acc", "joint_acc_ang", "lambda_n", "lambda_t", "prev_active"]
 
 
+# K2D_ORACLE_SANITIZE=1 builds and loads a second library, compiled with AddressSanitizer and
+# UndefinedBehaviorSanitizer (host code only), to run the CPU test suite under:
+#   LD_PRELOAD="$(g++ -print-file-name=libasan.so):$LD_PRELOAD" ASAN_OPTIONS=detect_leaks=0 \
+#   K2D_ORACLE_SANITIZE=1 python -m pytest tests -q -m "not gpu"
+SANITIZE = os.environ.get("K2D_ORACLE_SANITIZE", "") not in ("", "0")
+if SANITIZE:
+    _LIB = os.path.join(_HERE, "libk2d_oracle_san.so")
+
+
 def build(force=False):
     """Compile the oracle with plain g++ (-O2, no contraction of a*b+c into fma)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fPIC", "-shared", "-pthread",
                "-o", _LIB, _SRC]
+        if SANITIZE:
+            cmd[1:2] = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                        "-fno-omit-frame-pointer"]
         try:   # std::fma as one instruction where the host has it (a libm call gives the same bits, slowly)
             if " fma " in open("/proc/cpuinfo").read():
                 cmd.insert(1, "-mfma")

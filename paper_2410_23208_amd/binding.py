@@ -59,6 +59,7 @@ def lib():
         L.k2d_get_layout.argtypes = [ctypes.POINTER(k2d_caps), ctypes.POINTER(k2d_layout)]
         L.k2d_state_bytes.restype = ctypes.c_size_t
         L.k2d_state_bytes.argtypes = [ctypes.POINTER(k2d_caps), i32]
+        L.k2d_obs_dim.argtypes = [ctypes.POINTER(k2d_caps)]
         L.k2d_alloc_batch.argtypes = [ctypes.POINTER(k2d_caps), ctypes.POINTER(k2d_params), i32, vp, ctypes.c_size_t,
                                       ctypes.POINTER(vp)]
         L.k2d_free_batch.argtypes = [vp]
@@ -78,7 +79,7 @@ def lib():
     return _lib
 
 
-EXPORTS = ["k2d_get_layout", "k2d_state_bytes", "k2d_alloc_batch", "k2d_free_batch", "k2d_reset", "k2d_step",
+EXPORTS = ["k2d_get_layout", "k2d_obs_dim", "k2d_state_bytes", "k2d_alloc_batch", "k2d_free_batch", "k2d_reset", "k2d_step",
            "k2d_step_noalloc", "k2d_step_reset", "k2d_read_outcome", "k2d_read_entities", "k2d_decode_actions",
            "k2d_read_obs", "k2d_read_contacts", "k2d_read_health", "k2d_read_state", "k2d_write_state"]
 
@@ -105,6 +106,11 @@ def get_layout(caps):
     _check(lib().k2d_get_layout(ctypes.byref(c), ctypes.byref(out)), "k2d_get_layout")
     d = {n: getattr(out, n if n != "lambda" else "lambda_") for n in _LAYOUT_FIELDS}
     return d
+
+
+def obs_dim(caps):
+    c = make_caps(caps)
+    return lib().k2d_obs_dim(ctypes.byref(c))
 
 
 def state_bytes(caps, n_envs):

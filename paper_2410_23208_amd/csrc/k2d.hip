@@ -1877,6 +1877,11 @@ int k2d_get_layout(const k2d_caps* caps, k2d_layout* out) {
   return K2D_OK;
 }
 
+int k2d_obs_dim(const k2d_caps* caps) {
+  if (caps_class(caps) < 0) return -1;
+  return make_layout(caps->n_polygons, caps->n_circles, caps->n_joints, caps->n_thrusters).obs_dim;
+}
+
 size_t k2d_state_bytes(const k2d_caps* caps, int n_envs) {
   int cls = caps_class(caps);
   if (cls < 0 || n_envs < 1) return 0;

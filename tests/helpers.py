@@ -130,3 +130,75 @@ def energy(sc, state, g):
     ke = 0.5 * m * v2 + 0.5 * I * state["omega"] ** 2
     pe = m * (-g) * state["pos"].reshape(im.shape + (2,))[..., 1]
     return (ke + pe).sum(-1)
+
+
+# ---------------------------------------------------------------------------------------------------
+# Degenerate scenes (input that the engine must give a defined result for): the CPU pins and the GPU
+# parity tests run the same ones.
+# ---------------------------------------------------------------------------------------------------
+DEGENERATE_TRI = np.array([[-0.3, -0.1], [0.3, -0.1], [0.0, 0.2]])      # centred on its centroid
+
+
+def degenerate_scene(kind):
+    """(caps, params, scene, sane twin or None, steps): `kind` in coincident_circles, zero_length_edge,
+    joint_on_itself, indices_out_of_range, infinite_inverse_mass.  The twin is the well-formed scene that the
+    degenerate one must behave like, where there is one."""
+    caps = scenegen.CAPS["M"]                      # 6 polygons, 3 circles, 2 joints, 2 thrusters
+    prm = params(n_substeps=2, n_iters=6)
+    twin = None
+    sb = SceneBuilder(caps)
+    floor = sb.box(5.0, 0.1, (0.0, 0.0), static=True)
+    if kind == "coincident_circles":
+        sb.circle(0.25, (0.5, 1.0))
+        sb.circle(0.25, (0.5, 1.0), density=2.0)   # same centre: the printed normal is 0 / 0
+        sb.box(0.3, 0.2, (-1.0, 0.4))
+        sc = sb.scene()
+    elif kind == "zero_length_edge":
+        # a "quadrilateral" whose last two vertices coincide: one edge has no length, its normal is 0 / 0
+        quad = np.vstack([DEGENERATE_TRI, DEGENERATE_TRI[2:3]])
+        p = sb.polygon(DEGENERATE_TRI, (0.0, 0.6), theta=0.4)
+        sb.circle(0.2, (0.05, 1.05))
+        sb.circle(0.15, (-0.6, 0.3))
+        sb.box(0.3, 0.2, (1.5, 0.35))
+        twin = sb.scene()
+        sc = {k: v.copy() for k, v in twin.items()}
+        sc["n_verts"][0, p] = 4
+        sc["verts"][0, p] = scenegen.to_f32(dict(v=quad))["v"]
+    elif kind == "joint_on_itself":
+        a = sb.box(0.3, 0.2, (0.0, 0.5), theta=0.2)
+        b = sb.box(0.25, 0.25, (1.0, 0.8))
+        sb.circle(0.2, (0.1, 1.1))
+        sb.joint(a, b, (0.5, 0.6), motor_on=True, speed=2.0, power=0.4)
+        sb.joint(a, b, (0.2, 0.5), fixed=True)
+        sc = sb.scene()
+        twin = {k: v.copy() for k, v in sc.items()}
+        sc["joint_b"][0, 1] = sc["joint_a"][0, 1]          # both ends on shape a
+        twin["joint_active"][0, 1] = 0
+    elif kind == "indices_out_of_range":
+        a = sb.box(0.3, 0.2, (0.0, 0.5), theta=0.2)
+        b = sb.box(0.25, 0.25, (1.0, 0.8))
+        c = sb.circle(0.2, (0.1, 1.1))
+        sb.joint(a, b, (0.5, 0.6), motor_on=True, speed=2.0, power=0.4)
+        sb.joint(b, c, (0.6, 0.9))
+        sb.thruster(a, (0.1, 0.0), 0.5, 2.0)
+        sb.thruster(b, (0.0, 0.1), -1.0, 3.0)
+        sc = sb.scene()
+        twin = {k: v.copy() for k, v in sc.items()}
+        sc["joint_a"][0, 0] = 99
+        sc["joint_b"][0, 1] = -3
+        sc["thruster_body"][0, 1] = 77
+        twin["joint_active"][0, :] = 0
+        twin["thruster_active"][0, 1] = 0
+    elif kind == "infinite_inverse_mass":
+        bad = sb.box(0.3, 0.2, (0.0, 0.25))               # touches the floor: the first impulse is infinite
+        sb.circle(0.2, (2.0, 1.0))
+        sc = sb.scene()
+        sc["inv_mass"][0, bad] = np.inf
+    else:
+        raise KeyError(kind)
+    return caps, prm, sc, twin, 20
+
+
+def same_bits_or_both_nan(x, y):
+    x, y = np.asarray(x), np.asarray(y)
+    return x.shape == y.shape and bool(np.all((x == y) | (np.isnan(x) & np.isnan(y))))

@@ -35,6 +35,7 @@ def test_layout_matches_header_and_table4():
         assert L["scene_words"] == 12 * (P + C) + 9 * P + C + 15 * J + 6 * T
         assert L["lambda"] % 4 == 0 and L["state_words"] == L["pair_state"] + (n_pairs + 3) // 4
         assert L["obs_dim"] == 23 * P + 15 * C + 11 * J + 6 * T
+        assert binding.obs_dim(caps) == L["obs_dim"]
         assert k2d.state_bytes(caps, 10) >= 10 * 4 * L["state_words"]
         assert k2d.state_bytes(caps, 1000) < 1000 * k2d.state_bytes(caps, 1)      # records + a small per-environment tail
 
@@ -45,6 +46,7 @@ def test_argument_errors_without_device_work():
     out = binding.k2d_layout()
     assert lib.k2d_get_layout(ctypes.byref(bad), ctypes.byref(out)) == -2        # K2D_E_CAP
     assert lib.k2d_get_layout(None, ctypes.byref(out)) == -1                      # K2D_E_ARG
+    assert lib.k2d_obs_dim(ctypes.byref(bad)) == -1 and lib.k2d_obs_dim(None) == -1
     assert k2d.state_bytes((3, 3, 3, 3), 4) == 0 and k2d.state_bytes((5, 2, 1, 1), 0) == 0
     import scenegen
     caps = binding.make_caps((5, 2, 1, 1))

@@ -167,3 +167,93 @@ def test_health_flags_non_finite_active_shapes_only():
     vel[5, 0] = 3.0e38              # huge but finite: fine
     bad, count = k2d_env.health(pos, theta, vel, omega, active)
     assert bad.tolist() == [0, 1, 1, 0, 1, 0] and count == 3
+
+
+# ------------------------------------------------------------------ values of the flat observation
+def test_flat_observation_values_written_out_from_tables_5_to_7():
+    """Every slot of the engine's flat observation on a hand-built scene, against numbers typed in here from
+    the scene's definition and Tables 5-7: position 2, velocity 2, inverse mass, inverse inertia, density,
+    tanh(angular velocity / 10), sin and cos of the rotation, friction, restitution, then radius (circle) or
+    the 8 vertex coordinates and the vertex count (polygon), active, role; joints and thrusters as tabled.
+    The transcendental slots are checked against double-precision libm (the engine's fp32 routines are within
+    1.5e-7 of it), so swapping the sin / cos slots, or dropping the "/ 10", fails here."""
+    caps = (2, 1, 1, 1)
+    sb = SceneBuilder(caps)
+    tri_v = np.array([[-0.3, -0.1], [0.3, -0.1], [0.0, 0.2]])          # centred on its centroid, area 0.09
+    tri = sb.polygon(tri_v, (1.25, 2.5), theta=0.3, vel=(0.5, -0.75), omega=5.0, density=2.0, friction=0.7,
+                     restitution=0.15, role=2)
+    box = sb.box(0.4, 0.1, (-1.0, 0.5), theta=-1.2, vel=(0.0, 0.25), omega=-20.0, density=0.5, friction=0.3,
+                 restitution=0.05, role=1)
+    cir = sb.circle(0.25, (3.0, 1.5), theta=2.0, vel=(-1.5, 0.0), omega=0.5, density=4.0, friction=0.9,
+                    restitution=0.45, role=3)
+    sb.joint(tri, cir, (1.5, 2.5), motor_on=True, speed=2.5, power=0.75)
+    sb.thruster(box, (0.125, -0.05), angle=-0.6, power=1.75)
+    sc = sb.scene(f32=True)
+    o = Oracle(caps, 1, params(gravity_y=0.0), "f32")
+    o.load_scene(sc)
+    obs = o.obs()[0]
+    assert obs.shape == (23 * 2 + 15 + 11 + 6,)
+    f = np.float32
+
+    def close(x, want):
+        assert abs(float(x) - want) < 3e-7, (float(x), want)
+
+    # ---- the triangle: mass = density * area = 2 * 0.09; polar moment about the centroid of a triangle with
+    # vertices r_i: (m / 6) * (|r0|^2 + |r1|^2 + |r2|^2 + r0.r1 + r1.r2 + r2.r0)
+    t = obs[0:23]
+    assert [t[0], t[1], t[2], t[3]] == [f(1.25), f(2.5), f(0.5), f(-0.75)]
+    m_tri = 2.0 * 0.09
+    r = tri_v
+    i_tri = m_tri / 6.0 * (sum(r[i] @ r[i] for i in range(3)) + r[0] @ r[1] + r[1] @ r[2] + r[2] @ r[0])
+    close(t[4], 1.0 / m_tri)
+    assert abs(t[5] * i_tri - 1.0) < 1e-6
+    assert t[6] == f(2.0)
+    close(t[7], np.tanh(5.0 / 10.0))                                    # 0.46211715726
+    close(t[8], np.sin(0.3)); close(t[9], np.cos(0.3))                  # 0.29552020666, 0.95533648912
+    assert abs(float(t[7]) - 0.46211715726) < 3e-7 and abs(float(t[8]) - 0.29552020666) < 3e-7
+    assert abs(float(t[9]) - 0.95533648912) < 3e-7
+    assert [t[10], t[11]] == [f(0.7), f(0.15)]
+    assert list(t[12:20]) == [f(-0.3), f(-0.1), f(0.3), f(-0.1), f(0.0), f(0.2), f(0.0), f(0.0)]
+    assert [t[20], t[21], t[22]] == [3.0, 1.0, 2.0]                     # vertex count, active, role
+    # ---- the box 0.8 x 0.2: mass = 0.5 * 0.16, inertia = m (w^2 + h^2) / 12
+    b = obs[23:46]
+    assert [b[0], b[1], b[2], b[3]] == [f(-1.0), f(0.5), f(0.0), f(0.25)]
+    m_box = 0.5 * 0.16
+    close(b[4], 1.0 / m_box)
+    assert abs(b[5] * (m_box * (0.8 ** 2 + 0.2 ** 2) / 12.0) - 1.0) < 1e-6
+    assert b[6] == f(0.5)
+    close(b[7], np.tanh(-2.0))                                          # -0.96402758007
+    close(b[8], np.sin(-1.2)); close(b[9], np.cos(-1.2))                # -0.93203908597, 0.36235775448
+    assert abs(float(b[8]) + 0.93203908597) < 3e-7 and abs(float(b[9]) - 0.36235775448) < 3e-7
+    assert [b[10], b[11]] == [f(0.3), f(0.05)]
+    assert list(b[12:20]) == [f(-0.4), f(-0.1), f(0.4), f(-0.1), f(0.4), f(0.1), f(-0.4), f(0.1)]
+    assert [b[20], b[21], b[22]] == [4.0, 1.0, 1.0]
+    # ---- the circle: mass = density * pi r^2, inertia = m r^2 / 2
+    c = obs[46:61]
+    assert [c[0], c[1], c[2], c[3]] == [f(3.0), f(1.5), f(-1.5), f(0.0)]
+    m_c = 4.0 * np.pi * 0.25 ** 2
+    assert abs(c[4] * m_c - 1.0) < 1e-6 and abs(c[5] * (0.5 * m_c * 0.25 ** 2) - 1.0) < 1e-6
+    assert c[6] == f(4.0)
+    close(c[7], np.tanh(0.05)); close(c[8], np.sin(2.0)); close(c[9], np.cos(2.0))   # 0.04995837, 0.90929743, -0.41614684
+    assert abs(float(c[9]) + 0.41614683655) < 3e-7
+    assert [c[10], c[11], c[12], c[13], c[14]] == [f(0.9), f(0.45), f(0.25), 1.0, 3.0]
+    # ---- the joint: active, fixed, anchor on a (local frame of the triangle: world offset (0.25, 0) turned by
+    # -0.3), anchor on b (world offset (-1.5, 1.0) turned by -2.0), motor power, motor speed, motor on,
+    # sin / cos of rotation(a) - rotation(b) = 0.3 - 2.0
+    j = obs[61:72]
+    assert [j[0], j[1]] == [1.0, 0.0]
+    close(j[2], 0.25 * np.cos(0.3)); close(j[3], -0.25 * np.sin(0.3))
+    close(j[4], -1.5 * np.cos(2.0) + 1.0 * np.sin(2.0)); close(j[5], 1.5 * np.sin(2.0) + 1.0 * np.cos(2.0))
+    assert [j[6], j[7], j[8]] == [f(0.75), f(2.5), 1.0]
+    close(j[9], np.sin(-1.7)); close(j[10], np.cos(-1.7))               # -0.99166481045, -0.12884449430
+    assert abs(float(j[9]) + 0.99166481045) < 3e-7 and abs(float(j[10]) + 0.12884449430) < 3e-7
+    # ---- the thruster: active, mount point (local), power, sin / cos of its local angle
+    th = obs[72:78]
+    assert [th[0], th[1], th[2], th[3]] == [1.0, f(0.125), f(-0.05), f(1.75)]
+    close(th[4], np.sin(-0.6)); close(th[5], np.cos(-0.6))              # -0.56464247340, 0.82533561491
+    assert abs(float(th[4]) + 0.56464247340) < 3e-7 and abs(float(th[5]) - 0.82533561491) < 3e-7
+    # an inactive shape keeps its slots and reports active = 0
+    sc2 = {k: v.copy() for k, v in sc.items()}
+    sc2["active"][0, box] = 0
+    o.load_scene(sc2)
+    assert o.obs()[0][23 + 21] == 0.0 and o.obs()[0][21] == 1.0
