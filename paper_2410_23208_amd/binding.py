@@ -49,33 +49,43 @@ class k2d_layout(ctypes.Structure):
 _lib = None
 
 
+def _declare(L):
+    vp, i32 = ctypes.c_void_p, ctypes.c_int
+    L.k2d_get_layout.argtypes = [ctypes.POINTER(k2d_caps), ctypes.POINTER(k2d_layout)]
+    L.k2d_obs_dim.argtypes = [ctypes.POINTER(k2d_caps)]
+    L.k2d_state_bytes.restype = ctypes.c_size_t
+    L.k2d_state_bytes.argtypes = [ctypes.POINTER(k2d_caps), i32]
+    L.k2d_alloc_batch.argtypes = [ctypes.POINTER(k2d_caps), ctypes.POINTER(k2d_params), i32, vp, ctypes.c_size_t,
+                                  ctypes.POINTER(vp)]
+    L.k2d_free_batch.argtypes = [vp]
+    L.k2d_reset.argtypes = [vp, vp, vp, i32, vp]
+    L.k2d_step.argtypes = [vp, vp, i32, i32, vp]
+    L.k2d_step_noalloc.argtypes = [vp, vp, i32, i32, vp]
+    L.k2d_step_reset.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp]
+    L.k2d_read_obs.argtypes = [vp, vp, vp]
+    L.k2d_read_contacts.argtypes = [vp, vp, vp, vp]
+    L.k2d_read_entities.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+    L.k2d_decode_actions.argtypes = [ctypes.POINTER(k2d_caps), vp, vp, ctypes.c_size_t, vp]
+    L.k2d_read_outcome.argtypes = [vp, ctypes.POINTER(k2d_reward_params), vp, vp, vp, vp]
+    L.k2d_read_health.argtypes = [vp, vp, vp, vp]
+    L.k2d_read_state.argtypes = [vp, vp, vp]
+    L.k2d_write_state.argtypes = [vp, vp, vp]
+    return L
+
+
 def lib():
     """The loaded C-ABI library (built beforehand, in-tree)."""
     global _lib
     if _lib is None:
-        path = _build.ensure_built()
-        L = ctypes.CDLL(path)
-        vp, i32 = ctypes.c_void_p, ctypes.c_int
-        L.k2d_get_layout.argtypes = [ctypes.POINTER(k2d_caps), ctypes.POINTER(k2d_layout)]
-        L.k2d_state_bytes.restype = ctypes.c_size_t
-        L.k2d_state_bytes.argtypes = [ctypes.POINTER(k2d_caps), i32]
-        L.k2d_obs_dim.argtypes = [ctypes.POINTER(k2d_caps)]
-        L.k2d_alloc_batch.argtypes = [ctypes.POINTER(k2d_caps), ctypes.POINTER(k2d_params), i32, vp, ctypes.c_size_t,
-                                      ctypes.POINTER(vp)]
-        L.k2d_free_batch.argtypes = [vp]
-        L.k2d_reset.argtypes = [vp, vp, vp, i32, vp]
-        L.k2d_step.argtypes = [vp, vp, i32, i32, vp]
-        L.k2d_step_noalloc.argtypes = [vp, vp, i32, i32, vp]
-        L.k2d_step_reset.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp]
-        L.k2d_read_obs.argtypes = [vp, vp, vp]
-        L.k2d_read_contacts.argtypes = [vp, vp, vp, vp]
-        L.k2d_read_entities.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
-        L.k2d_decode_actions.argtypes = [ctypes.POINTER(k2d_caps), vp, vp, ctypes.c_size_t, vp]
-        L.k2d_read_outcome.argtypes = [vp, ctypes.POINTER(k2d_reward_params), vp, vp, vp, vp]
-        L.k2d_read_health.argtypes = [vp, vp, vp, vp]
-        L.k2d_read_state.argtypes = [vp, vp, vp]
-        L.k2d_write_state.argtypes = [vp, vp, vp]
-        _lib = L
+        _lib = _declare(ctypes.CDLL(_build.ensure_built()))
+    return _lib
+
+
+def use_library(path):
+    """Bind this module to another build of the same library (the instrumented build of phase_timers.py).
+    Call before any batch exists."""
+    global _lib
+    _lib = _declare(ctypes.CDLL(path))
     return _lib
 
 

@@ -17,9 +17,14 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
 HEADER = os.path.join(ROOT, "include", "k2d.h")
 
 
-def build(verbose=False):
+LIB_TIMERS = os.path.join(HERE, "libk2d_timers.so")
+
+
+def build(verbose=False, phase_timers=False):
+    """Compiles the library; phase_timers=True builds the instrumented twin (libk2d_timers.so, compiled with
+    -DK2D_PHASE_TIMERS: the step kernel records the clocks of its phases) that phase_timers.py uses."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + ["-o", LIB, SRC]
+    cmd = [hipcc] + FLAGS + (["-DK2D_PHASE_TIMERS", "-o", LIB_TIMERS, SRC] if phase_timers else ["-o", LIB, SRC])
     if verbose:
         print(" ".join(cmd))
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
@@ -27,7 +32,7 @@ def build(verbose=False):
         raise RuntimeError("hipcc failed (exit %d):\n%s\n%s" % (r.returncode, r.stdout[-4000:], r.stderr[-8000:]))
     if verbose:
         print(r.stderr)
-    return LIB
+    return LIB_TIMERS if phase_timers else LIB
 
 
 def stale():

@@ -40,6 +40,21 @@
 
 #include "k2d.h"
 
+// Phase clocks (builds with -DK2D_PHASE_TIMERS only; the product library has none of this): every
+// wavefront adds up the shader clocks it spends in each phase of a substep and leaves the sums, followed
+// by its totals of collision and joint dependency levels, in a caller-owned device buffer
+// (k2d_debug_set_phase_buffer), kPhaseSlots 64-bit words per wavefront.
+#ifdef K2D_PHASE_TIMERS
+#define K2D_T(i) { const long long t_now_ = clock64(); t_acc[i] += t_now_ - t_last; t_last = t_now_; }
+#else
+#define K2D_T(i)
+#endif
+enum {   // phases of one substep, in the order they run
+  kT_Actions = 0, kT_Shapes, kT_JointConstants, kT_External, kT_Cull, kT_Manifolds, kT_Presolve, kT_Levels,
+  kT_WarmStart, kT_SweepJoints, kT_SweepPairs, kT_Euler, kT_CorrectPairs, kT_CorrectJoints, kT_Restart, kT_Count
+};
+constexpr int kPhaseSlots = kT_Count + 2;
+
 namespace {
 
 constexpr int kRecW = 25;  // words of one active-pair record (see PairRec)
@@ -655,7 +670,11 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
                                                       int n_envs, int n_steps, Params prm,
                                                       const float* __restrict__ levels, int n_level_records,
                                                       const int32_t* __restrict__ reset_level,
-                                                      const int32_t* __restrict__ order) {
+                                                      const int32_t* __restrict__ order
+#ifdef K2D_PHASE_TIMERS
+                                                      , unsigned long long* __restrict__ phase_clocks
+#endif
+                                                      ) {
   using S = Step<K>;
   constexpr k2d_layout L = K::L;
   constexpr int N = K::N, P = K::P, J = K::J, T = K::T, G = K::G, R = K::R, GP = K::GP, H = K::H;
@@ -689,6 +708,11 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
   for (int r = 0; r < R; ++r)
     if (r % H == rpar) my_r |= 1u << r;
 
+#ifdef K2D_PHASE_TIMERS
+  long long t_acc[kT_Count] = {};
+  long long t_last = clock64();
+  unsigned long long t_pair_levels = 0, t_joint_levels = 0;
+#endif
   int step = 0;
   bool first = true;
   do {   // (one pass, unless environments are re-initialised on the way)
@@ -852,6 +876,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     }
     if (prm.clip_thr) act_t = fminf(fmaxf(act_t, 0.f), 1.f);
 
+    K2D_T(kT_Actions);
     for (int sub = 0; sub < prm.n_substeps; ++sub) {
       // ---- gravity (Alg. 1) and world-frame polygons ----
       for (int i = k; i < N; i += G) {
@@ -881,6 +906,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       }
       wave_sync();
 
+      K2D_T(kT_Shapes);
       // ---- joint constants of this substep; motor and thruster impulses from the same velocities ----
       float j_rax = 0.f, j_ray = 0.f, j_rbx = 0.f, j_rby = 0.f, j_k11 = 0.f, j_k12 = 0.f, j_k22 = 0.f;
       float j_idet = 0.f, j_bx = 0.f, j_by = 0.f, j_angm = 0.f, j_angb = 0.f, j_exc = 0.f, motor = 0.f;
@@ -923,6 +949,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         float f = t_power * act_t * h;
         t_ix = f * dx; t_iy = f * dy;
       }
+      K2D_T(kT_JointConstants);
       wave_sync();
       for (int lv = 0; lv < wave_levels; ++lv) {
         if (k < J && j_live && j_level == lv && motor != 0.f) {
@@ -941,6 +968,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         wave_sync();
       }
 
+      K2D_T(kT_External);
       // ---- collision manifolds of all eligible pairs (A.3.1-A.3.4) and their substep constants ----
       // 1. the cheap test for all of this lane's pairs: bounding circles apart (with margin) means no
       //    manifold point can have positive penetration;
@@ -988,6 +1016,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         for (unsigned mm = m2; mm != 0u; mm &= mm - 1u) cand_list[w2++] = (unsigned char)((__ffs(mm) - 1) * GP + kp);
       }
       wave_sync();
+      K2D_T(kT_Cull);
       int pool_base = 0;
       for (int kind = 0; kind < 3; ++kind) {
        const int n_kind = kind_n[kind], off_kind = kind_off[kind];
@@ -1043,6 +1072,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
        }
       }
       wave_sync();
+      K2D_T(kT_Manifolds);
       // lane k keeps active pairs k and G + k of its environment in registers
       typename S::Own oa, ob;
       oa.id = -1; ob.id = -1; oa.lv = -1; ob.lv = -1;
@@ -1052,6 +1082,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         if (k + G < pool_base && k + G < K::NREG) S::take_own(E, Rg, prm, k + G, static_mask, ob);
       }
       wave_sync();
+      K2D_T(kT_Presolve);
       // Dependency levels of the active pairs.  Walking the pairs in canonical order (round by round), a
       // pair goes one level after the last earlier pair that shares a movable shape with it.  Pairs of
       // one level touch disjoint movable shapes and pairs that share one keep their canonical order, so
@@ -1119,6 +1150,10 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         }
       };
 
+      K2D_T(kT_Levels);
+#ifdef K2D_PHASE_TIMERS
+      t_pair_levels += wave_clevels; t_joint_levels += wave_levels;
+#endif
       // ---- warm starting (Alg. 1, A.7): collisions in canonical order, then joints ----
       if (prm.warm_start) {
         for_each_level([&](typename S::Own& o) { S::template visit_own<true>(E, o); },
@@ -1146,6 +1181,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         }
       }
 
+      K2D_T(kT_WarmStart);
       // ---- solver sweeps (Alg. 1): joints, then collisions ----
       const int n_b = BATCHED ? prm.n_batches : 1;
       int oa_bj = 0, ob_bj = 0;   // batched schedule: batch and place of the two points of the held pairs
@@ -1185,6 +1221,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
           }
           wave_sync();
         }
+        K2D_T(kT_SweepJoints);
         if constexpr (BATCHED) {
           // A.8: the points of batch b are solved from the velocities the batch starts with, their impulses
           // staged by their place in the batch; then lane s applies to shape s, in place order, the
@@ -1288,6 +1325,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
                            for (int z = 0; z < 2; ++z) { rp[5 + 10 * z + 8] = rc.lam_n[z]; rp[5 + 10 * z + 9] = rc.lam_t[z]; }
                          }
                        });
+        K2D_T(kT_SweepPairs);
       }
 
       // ---- Euler step of position and rotation (Alg. 1) ----
@@ -1305,6 +1343,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       }
       wave_sync();
 
+      K2D_T(kT_Euler);
       // ---- positional corrections (A.3.7, A.4.1); the pair's accumulated impulses go to HBM ----
       auto correct = [&](float nx, float ny, float corr, int ab, float4 lam) {
         const int a = ab & 0xff, b = (ab >> 8) & 0xff;
@@ -1331,6 +1370,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
                          correct(rp[0], rp[1], rp[3], f2i(rp[4]), make_float4(rp[13], rp[14], rp[23], rp[24]));
                        }
                      });
+      K2D_T(kT_CorrectPairs);
       for (int lv = 0; lv < wave_levels; ++lv) {
         if (k < J && j_live && j_level == lv) {
           float ca = E[K::X_COS + ja], sa = E[K::X_SIN + ja], cb = E[K::X_COS + jb], sb = E[K::X_SIN + jb];
@@ -1346,6 +1386,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         }
         wave_sync();
       }
+      K2D_T(kT_CorrectJoints);
     }
     if (RESET) {   // new episodes (wave-uniform branch: the wavefront leaves the step loop together)
       int rl = env_ok ? reset_level[(size_t)step * n_envs + env] : -1;
@@ -1378,6 +1419,15 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
   first = false;
   } while (RESET && step < n_steps);
 
+#ifdef K2D_PHASE_TIMERS
+  K2D_T(kT_Restart);
+  if (phase_clocks && lane == 0) {
+    unsigned long long* out = phase_clocks + (size_t)blockIdx.x * kPhaseSlots;
+    for (int i = 0; i < kT_Count; ++i) out[i] = (unsigned long long)t_acc[i];
+    out[kT_Count] = t_pair_levels;
+    out[kT_Count + 1] = t_joint_levels;
+  }
+#endif
   // ---- write back: dynamic shape state, joint accumulators, pair states ----
   for (int e = 0; e < K::EPW; ++e) {
     const int env_e = env_of(slot0 + e);
@@ -1783,6 +1833,16 @@ int scratch_of_current_device(int32_t** out) {
   return K2D_OK;
 }
 
+// A kernel launch that records its own failure in `ok`: an error that an earlier, unrelated runtime call
+// of this thread left behind is read off first, so that it is not taken for this launch's.
+#define K2D_LAUNCH(ok, ...) \
+  do { (void)hipGetLastError(); hipLaunchKernelGGL(__VA_ARGS__); ok = (hipGetLastError() == hipSuccess) && ok; } while (0)
+
+#ifdef K2D_PHASE_TIMERS
+unsigned long long* g_phase_clocks = nullptr;   // caller-owned device buffer, kPhaseSlots words per wavefront
+long g_phase_waves = 0;
+#endif
+
 template <class K, bool RESET, bool BATCHED>
 int launch_step(float* state, const float* actions, int n_envs, int n_steps, const Params& prm, const float* levels,
                 int n_levels, const int32_t* reset_level, int32_t* order, int rec_words, const k2d_layout& layout,
@@ -1800,15 +1860,21 @@ int launch_step(float* state, const float* actions, int n_envs, int n_steps, con
     }
   }
   int grid = (n_envs + K::EPW - 1) / K::EPW;
+  bool ok = true;
   if (order) {   // (a launch of a few steps is not worth the ordering pass)
     int32_t* keys = order + grid * K::EPW;
-    hipLaunchKernelGGL(k2d_order_keys_kernel, dim3((n_envs + 255) / 256), dim3(256), 0, st, state, keys, n_envs, rec_words,
+    K2D_LAUNCH(ok, k2d_order_keys_kernel, dim3((n_envs + 255) / 256), dim3(256), 0, st, state, keys, n_envs, rec_words,
                        layout);
-    hipLaunchKernelGGL(k2d_order_kernel, dim3(1), dim3(1024), 0, st, keys, order, n_envs, grid * K::EPW);
+    K2D_LAUNCH(ok, k2d_order_kernel, dim3(1), dim3(1024), 0, st, keys, order, n_envs, grid * K::EPW);
   }
-  hipLaunchKernelGGL((k2d_step_kernel<K, RESET, BATCHED>), dim3(grid), dim3(64), K::LDS_BYTES, st, state, actions, n_envs,
+#ifdef K2D_PHASE_TIMERS
+  K2D_LAUNCH(ok, (k2d_step_kernel<K, RESET, BATCHED>), dim3(grid), dim3(64), K::LDS_BYTES, st, state, actions, n_envs,
+                     n_steps, prm, levels, n_levels, reset_level, order, grid <= g_phase_waves ? g_phase_clocks : nullptr);
+#else
+  K2D_LAUNCH(ok, (k2d_step_kernel<K, RESET, BATCHED>), dim3(grid), dim3(64), K::LDS_BYTES, st, state, actions, n_envs,
                      n_steps, prm, levels, n_levels, reset_level, order);
-  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+#endif
+  return ok ? K2D_OK : K2D_E_HIP;
 }
 
 }  // namespace
@@ -1870,6 +1936,17 @@ static int step_launch(k2d_batch* b, const float* actions_dev, int n_envs, int n
 
 extern "C" {
 
+#ifdef K2D_PHASE_TIMERS
+// Instrumented build only: where the step kernel leaves its phase clocks (device memory, kPhaseSlots
+// 64-bit words for each of n_waves wavefronts; a launch with more wavefronts than that records nothing).
+// Returns the number of words per wavefront.
+int k2d_debug_set_phase_buffer(void* clocks_dev, long n_waves) {
+  g_phase_clocks = static_cast<unsigned long long*>(clocks_dev);
+  g_phase_waves = clocks_dev ? n_waves : 0;
+  return kPhaseSlots;
+}
+#endif
+
 int k2d_get_layout(const k2d_caps* caps, k2d_layout* out) {
   if (!caps || !out) return K2D_E_ARG;
   if (caps_class(caps) < 0) return K2D_E_CAP;
@@ -1923,9 +2000,10 @@ int k2d_free_batch(k2d_batch* batch) {
 int k2d_reset(k2d_batch* b, const void* scenes_dev, const int32_t* env_ids_dev, int n, void* stream) {
   if (!b || !scenes_dev || n < 1) return K2D_E_ARG;
   if (!env_ids_dev && n > b->n_envs) return K2D_E_SIZE;
-  hipLaunchKernelGGL(k2d_reset_kernel, dim3(n), dim3(256), 0, static_cast<hipStream_t>(stream), b->state,
+  bool ok = true;
+  K2D_LAUNCH(ok, k2d_reset_kernel, dim3(n), dim3(256), 0, static_cast<hipStream_t>(stream), b->state,
                      static_cast<const float*>(scenes_dev), env_ids_dev, n, b->n_envs, b->rec_words, b->layout);
-  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+  return ok ? K2D_OK : K2D_E_HIP;
 }
 
 int k2d_step(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, void* stream) {
@@ -1957,18 +2035,20 @@ int k2d_read_obs(k2d_batch* b, float* obs_dev, void* stream) {
   if (!b || !obs_dev) return K2D_E_ARG;
   const k2d_caps& c = b->caps;
   long n = (long)b->n_envs * (c.n_polygons + c.n_circles + c.n_joints + c.n_thrusters);
-  hipLaunchKernelGGL(k2d_obs_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+  bool ok = true;
+  K2D_LAUNCH(ok, k2d_obs_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
                      b->state, obs_dev, b->n_envs, b->rec_words, b->layout, c.n_polygons, c.n_circles, c.n_joints,
                      c.n_thrusters);
-  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+  return ok ? K2D_OK : K2D_E_HIP;
 }
 
 int k2d_read_contacts(k2d_batch* b, uint8_t* pair_count_dev, uint32_t* shape_adj_dev, void* stream) {
   if (!b) return K2D_E_ARG;
   if (!pair_count_dev && !shape_adj_dev) return K2D_OK;
-  hipLaunchKernelGGL(k2d_contacts_kernel, dim3(b->n_envs), dim3(128), 0, static_cast<hipStream_t>(stream), b->state,
+  bool ok = true;
+  K2D_LAUNCH(ok, k2d_contacts_kernel, dim3(b->n_envs), dim3(128), 0, static_cast<hipStream_t>(stream), b->state,
                      pair_count_dev, shape_adj_dev, b->n_envs, b->rec_words, b->layout);
-  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+  return ok ? K2D_OK : K2D_E_HIP;
 }
 
 int k2d_read_entities(k2d_batch* b, float* shapes_dev, float* joints_dev, int32_t* joint_idx_dev, float* thrusters_dev,
@@ -1980,12 +2060,13 @@ int k2d_read_entities(k2d_batch* b, float* shapes_dev, float* joints_dev, int32_
   if (b->layout.n_shapes > 16) return K2D_E_CAP;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const long n = (long)b->n_envs * (c.n_polygons + c.n_circles + 2 * c.n_joints + c.n_thrusters);
-  hipLaunchKernelGGL(k2d_entities_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, b->state, shapes_dev,
+  bool ok = true;
+  K2D_LAUNCH(ok, k2d_entities_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, b->state, shapes_dev,
                      joints_dev, joint_idx_dev, thrusters_dev, thruster_idx_dev, b->n_envs, b->rec_words, b->layout,
                      c.n_polygons, c.n_circles, c.n_joints, c.n_thrusters);
-  hipLaunchKernelGGL(k2d_masks_kernel, dim3((b->n_envs + 3) / 4), dim3(64), 0, st, b->state, masks_dev, b->n_envs,
+  K2D_LAUNCH(ok, k2d_masks_kernel, dim3((b->n_envs + 3) / 4), dim3(64), 0, st, b->state, masks_dev, b->n_envs,
                      b->rec_words, b->layout, c.n_joints);
-  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+  return ok ? K2D_OK : K2D_E_HIP;
 }
 
 int k2d_decode_actions(const k2d_caps* caps, const int32_t* discrete_dev, float* actions_dev, size_t n_rows,
@@ -1995,44 +2076,49 @@ int k2d_decode_actions(const k2d_caps* caps, const int32_t* discrete_dev, float*
   const int A = caps->n_joints + caps->n_thrusters;
   const size_t n = n_rows * (size_t)A;
   if (n == 0) return K2D_OK;
-  hipLaunchKernelGGL(k2d_decode_actions_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+  bool ok = true;
+  K2D_LAUNCH(ok, k2d_decode_actions_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
                      static_cast<hipStream_t>(stream), discrete_dev, actions_dev, n, caps->n_joints, A);
-  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+  return ok ? K2D_OK : K2D_E_HIP;
 }
 
 int k2d_read_outcome(k2d_batch* b, const k2d_reward_params* rp, float* dist_dev, float* reward_dev, uint8_t* done_dev,
                      void* stream) {
   if (!b || !rp || !dist_dev || !reward_dev || !done_dev) return K2D_E_ARG;
   if (b->layout.n_shapes > 16) return K2D_E_CAP;
-  hipLaunchKernelGGL(k2d_outcome_kernel, dim3((b->n_envs + 3) / 4), dim3(64), 0, static_cast<hipStream_t>(stream),
+  bool ok = true;
+  K2D_LAUNCH(ok, k2d_outcome_kernel, dim3((b->n_envs + 3) / 4), dim3(64), 0, static_cast<hipStream_t>(stream),
                      b->state, dist_dev, reward_dev, done_dev, b->n_envs, b->rec_words, b->layout, rp->kappa,
                      rp->role_green, rp->role_blue, rp->role_red);
-  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+  return ok ? K2D_OK : K2D_E_HIP;
 }
 
 int k2d_read_health(k2d_batch* b, uint8_t* bad_dev, int32_t* count_dev, void* stream) {
   if (!b || !bad_dev || !count_dev) return K2D_E_ARG;
   if (b->layout.n_shapes > 16) return K2D_E_CAP;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  hipLaunchKernelGGL(k2d_zero_word_kernel, dim3(1), dim3(1), 0, st, count_dev);
-  hipLaunchKernelGGL(k2d_health_kernel, dim3((b->n_envs + 3) / 4), dim3(64), 0, st, b->state, bad_dev, count_dev,
+  bool ok = true;
+  K2D_LAUNCH(ok, k2d_zero_word_kernel, dim3(1), dim3(1), 0, st, count_dev);
+  K2D_LAUNCH(ok, k2d_health_kernel, dim3((b->n_envs + 3) / 4), dim3(64), 0, st, b->state, bad_dev, count_dev,
                      b->n_envs, b->rec_words, b->layout);
-  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+  return ok ? K2D_OK : K2D_E_HIP;
 }
 
 int k2d_read_state(k2d_batch* b, void* records_dev, void* stream) {
   if (!b || !records_dev) return K2D_E_ARG;
-  hipLaunchKernelGGL(k2d_copy_state_kernel, dim3(b->n_envs), dim3(256), 0, static_cast<hipStream_t>(stream), b->state,
+  bool ok = true;
+  K2D_LAUNCH(ok, k2d_copy_state_kernel, dim3(b->n_envs), dim3(256), 0, static_cast<hipStream_t>(stream), b->state,
                      static_cast<float*>(records_dev), b->n_envs, b->rec_words, b->layout, 0);
-  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+  return ok ? K2D_OK : K2D_E_HIP;
 }
 
 int k2d_write_state(k2d_batch* b, const void* records_dev, void* stream) {
   if (!b || !records_dev) return K2D_E_ARG;
-  hipLaunchKernelGGL(k2d_copy_state_kernel, dim3(b->n_envs), dim3(256), 0, static_cast<hipStream_t>(stream), b->state,
+  bool ok = true;
+  K2D_LAUNCH(ok, k2d_copy_state_kernel, dim3(b->n_envs), dim3(256), 0, static_cast<hipStream_t>(stream), b->state,
                      const_cast<float*>(static_cast<const float*>(records_dev)), b->n_envs, b->rec_words,
                      b->layout, 1);
-  return hipGetLastError() == hipSuccess ? K2D_OK : K2D_E_HIP;
+  return ok ? K2D_OK : K2D_E_HIP;
 }
 
 }  // extern "C"
