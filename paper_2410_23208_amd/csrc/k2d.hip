@@ -58,6 +58,7 @@ constexpr int kPhaseSlots = kT_Count + 2;
 namespace {
 
 constexpr int kRecW = 25;  // words of one active-pair record (see PairRec)
+constexpr float kCullMargin = 1e-3f;   // by how much every bounding box is grown before the overlap test
 
 constexpr int align_up(int x, int a) { return (x + a - 1) / a * a; }
 
@@ -129,9 +130,11 @@ struct Cfg {
                 "capacity class does not fit the lane mapping");
   // Active pairs are numbered 0, 1, ... as the narrowphase finds them.  Pairs below NREG live in
   // registers (lane k holds pairs k and G + k): the lane that found the manifold leaves it in an LDS
-  // staging slot, the lane that keeps the pair derives the substep constants from it.  The next POOL
-  // pairs live as full records in LDS, the rest in the HBM record.
-  static constexpr int NREG = 2 * G, POOL = 4, kManW = 9;
+  // staging slot, the lane that keeps the pair derives the substep constants from it.  Pairs beyond them
+  // live as full records in a small LDS pool (POOL records) or, past that, in the HBM record.
+  static constexpr int NREG = 2 * G, kManW = 9;
+  static constexpr int POOL = (NP > NREG && NP - NREG <= 4) ? NP - NREG : 0;   // (a class with few pairs beyond the
+                                                                               // registers keeps them all in LDS)
   static constexpr k2d_layout L = make_layout(P, C, J, T);
   // HBM record: state words, then room for the pair records that do not fit the LDS pool
   static constexpr int SPILL = (NP > NREG + POOL ? NP - NREG - POOL : 0);
@@ -140,8 +143,9 @@ struct Cfg {
   // LDS image of one environment: scene words, then derived data
   static constexpr int X_COS = align_up(L.scene_words, 2);
   static constexpr int X_SIN = X_COS + N;
-  static constexpr int X_BRAD = X_SIN + N;       // bounding radius of every shape
-  static constexpr int X_WV = align_up(X_BRAD + N, 2);     // world vertices, float2 [4][P]
+  static constexpr int X_BOX = align_up(X_SIN + N, 4);     // bounding box of every shape, float4 (min x, min y, max x, max y),
+                                                           // grown by kCullMargin on every side
+  static constexpr int X_WV = X_BOX + 4 * N;               // world vertices, float2 [4][P]
   static constexpr int X_WN = X_WV + 8 * P;                // outward unit edge normals, float2 [4][P]
   static constexpr int NID = R * GP;                       // pair ids: id = r * GP + k (canonical order)
   static constexpr int X_TABLE = align_up(X_WN + 8 * P, 4);        // bytes [NID]: number of the active pair with this id (set for the pairs not held in registers)
@@ -722,18 +726,6 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     k2d_sincos(E[L.theta + i], sn, cs);
     E[K::X_COS + i] = cs;
     E[K::X_SIN + i] = sn;
-    float br;
-    if (i < P) {
-      int nv = f2i(E[L.n_verts + i]);
-      br = 0.f;
-      for (int v = 0; v < 4; ++v) {
-        float lx = E[L.verts + (2 * v) * P + i], ly = E[L.verts + (2 * v + 1) * P + i];
-        if (v < nv) br = fmaxf(br, sqrtf(lx * lx + ly * ly));
-      }
-    } else {
-      br = E[L.radius + (i - P)];
-    }
-    E[K::X_BRAD + i] = br;
     E[K::X_JOINED + i] = i2f(0);
   }
   wave_sync();
@@ -860,6 +852,11 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     rp[r >> 2] |= e << (8 * (r & 3));
   }
   const bool movable = k < N && !((static_mask >> k) & 1u);
+  // Dependency levels of the collision constraints are kept from one substep to the next: they depend
+  // only on which pairs collide, and that set is the same in most consecutive substeps.
+  int n_clevels = 0;          // next free level of this lane's shape
+  int wave_clevels = 0;       // levels of the wavefront's deepest environment
+  bool levels_valid = false;  // false until the levels of the current set of colliding pairs are worked out
   unsigned* rmask = reinterpret_cast<unsigned*>(E + K::X_RMASK);
   unsigned char* lvl = reinterpret_cast<unsigned char*>(E + K::X_LVL);
   float* pool = E + K::X_POOL;
@@ -894,6 +891,11 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
           }
           if (nv == 3) { wx[3] = wx[0]; wy[3] = wy[0]; }   // a triangle's spare slot repeats vertex 0: the
                                                            // manifold code can then run over four vertices
+          *reinterpret_cast<float4*>(E + K::X_BOX + 4 * i) =
+              make_float4(fminf(fminf(wx[0], wx[1]), fminf(wx[2], wx[3])) - kCullMargin,
+                          fminf(fminf(wy[0], wy[1]), fminf(wy[2], wy[3])) - kCullMargin,
+                          fmaxf(fmaxf(wx[0], wx[1]), fmaxf(wx[2], wx[3])) + kCullMargin,
+                          fmaxf(fmaxf(wy[0], wy[1]), fmaxf(wy[2], wy[3])) + kCullMargin);
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             int v1 = (v + 1 == nv) ? 0 : ((v + 1) & 3);
@@ -902,6 +904,9 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
             *reinterpret_cast<float2*>(E + K::X_WV + 2 * (v * P + i)) = make_float2(wx[v], wy[v]);
             *reinterpret_cast<float2*>(E + K::X_WN + 2 * (v * P + i)) = make_float2(ey / len, -ex / len);
           }
+        } else {
+          const float px = E[L.pos_x + i], py = E[L.pos_y + i], r = E[L.radius + (i - P)] + kCullMargin;
+          *reinterpret_cast<float4*>(E + K::X_BOX + 4 * i) = make_float4(px - r, py - r, px + r, py + r);
         }
       }
       wave_sync();
@@ -970,23 +975,25 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
 
       K2D_T(kT_External);
       // ---- collision manifolds of all eligible pairs (A.3.1-A.3.4) and their substep constants ----
-      // 1. the cheap test for all of this lane's pairs: bounding circles apart (with margin) means no
-      //    manifold point can have positive penetration;
+      // 1. the cheap test for all of this lane's pairs: bounding boxes (of the very world vertices and
+      //    centres the manifolds use, grown by a margin a thousand times the rounding error of a
+      //    coordinate) that do not overlap mean no manifold point can have positive penetration;
       // 2. the surviving pair ids of the environment are gathered into one list, one shape-type mix
       //    after the other, so that the group's lanes share them evenly and a wavefront runs one kind
       //    of manifold code per trip;
       // 3. the manifold of every active pair is staged in LDS for the lane that keeps the pair in
       //    registers for the rest of the substep (pairs beyond two per lane become records in LDS / HBM).
       unsigned cand = 0u;
+      bool set_changed = false;   // a pair of this lane collides now and did not one substep ago, or the reverse
       {
         const unsigned ab_lo = (unsigned)my_ab, ab_hi = (unsigned)(my_ab >> 32);
 #pragma unroll
         for (int j = 0; j < (R + H - 1) / H; ++j) {   // round j * H + rpar: every lane is busy in every trip
           const unsigned pk = ((j < 4 ? ab_lo : ab_hi) >> (8 * (j & 3))) & 0xffu;
           const int a = pk & 15, b = pk >> 4;
-          float dx = E[L.pos_x + b] - E[L.pos_x + a], dy = E[L.pos_y + b] - E[L.pos_y + a];
-          float rr = (E[K::X_BRAD + a] + E[K::X_BRAD + b]) * 1.0001f + 1e-5f;
-          if (dx * dx + dy * dy <= rr * rr) cand |= 1u << (j * H + rpar);
+          const float4 ba = *reinterpret_cast<const float4*>(E + K::X_BOX + 4 * a);
+          const float4 bb = *reinterpret_cast<const float4*>(E + K::X_BOX + 4 * b);
+          if (ba.x <= bb.z && bb.x <= ba.z && ba.y <= bb.w && bb.y <= ba.w) cand |= 1u << (j * H + rpar);
         }
         cand &= elig;
       }
@@ -998,7 +1005,9 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
           unsigned w = r < 4 ? ps.x : r < 8 ? ps.y : r < 12 ? ps.z : ps.w;
           if ((w >> (8 * (r & 3))) & 0xffu) nz |= 1u << r;
         }
-        for (unsigned st = nz & ~cand & my_r; st != 0u; st &= st - 1u) pstate[kp * 16 + (__ffs(st) - 1)] = 0;
+        const unsigned gone = nz & ~cand & my_r;
+        set_changed = gone != 0u;
+        for (unsigned st = gone; st != 0u; st &= st - 1u) pstate[kp * 16 + (__ffs(st) - 1)] = 0;
       }
       if (k < 4) bitmap[k] = 0u;
       rmask[k] = 0u;
@@ -1040,13 +1049,14 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         }
         const bool act0 = m.valid[0] && m.pen[0] > 0.f, act1 = m.valid[1] && m.pen[1] > 0.f;
         const bool active = act0 || act1;
+        const int prev_bits = have ? (int)pstate[kk * 16 + r] : 0;   // which points collided one substep ago
+        set_changed |= have && ((prev_bits != 0) != active);
         unsigned long long bal = __ballot(active);
         unsigned envbits = (unsigned)(bal >> (g * G)) & (G >= 32 ? 0xffffffffu : ((1u << (G & 31)) - 1u));
         const int idx = pool_base + __popc(envbits & ((1u << k) - 1u));
         pool_base += __popc(envbits);
         if (active) {
-          const int w = a | (b << 8) | ((int)act0 << 16) | ((int)act1 << 17) | (id << 18) |
-                        ((int)pstate[kk * 16 + r] << 25);
+          const int w = a | (b << 8) | ((int)act0 << 16) | ((int)act1 << 17) | (id << 18) | (prev_bits << 25);
           if (idx < K::NREG) {   // staged for the lane that keeps it
             LdsF p = to_lds(E + K::X_STAGE + idx * K::kManW);
             p[0] = m.nx; p[1] = m.ny;
@@ -1090,8 +1100,8 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       // in far fewer trips (everything resting on the static floor is one level; a level never exceeds
       // the round).  Lane s follows shape s: in every round the two lanes of an active pair exchange the
       // next free level of their shapes and both move on to one past the larger.
-      int n_clevels = 0;   // next free level of this lane's shape
-      {
+      if (!levels_valid || __any(set_changed)) {
+        n_clevels = 0;
         const unsigned rm = rmask[k];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -1108,10 +1118,11 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
             }
           }
         }
+        wave_clevels = 0;
+        for (int lv = 1; lv <= R; ++lv)
+          if (__any(n_clevels >= lv)) wave_clevels = lv;
+        levels_valid = true;
       }
-      int wave_clevels = 0;
-      for (int lv = 1; lv <= R; ++lv)
-        if (__any(n_clevels >= lv)) wave_clevels = lv;
       wave_sync();
       if (oa.id >= 0) oa.lv = lvl[oa.id];
       if (ob.id >= 0) ob.lv = lvl[ob.id];
