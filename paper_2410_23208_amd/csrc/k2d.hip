@@ -637,7 +637,7 @@ struct Step {
   }
   // The lane that keeps pair idx picks its staged manifold up and derives the record in its own registers.
   static __device__ __forceinline__ void take_own(const float* E, const float* Rg, const Params& prm, int idx,
-                                                  unsigned fixed, Own& o) {
+                                                  unsigned fixed, int kept_id, float4 kept_lam, Own& o) {
     LdsCF p = (LdsCF)(E + K::X_STAGE + idx * K::kManW);
     Manifold m;
     m.nx = p[0]; m.ny = p[1];
@@ -646,8 +646,10 @@ struct Step {
     const int w = f2i(p[8]);
     const int a = w & 0xff, b = (w >> 8) & 0xff;
     float4 lam = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (prm.warm_start && ((w >> 25) & 3))
-      lam = *reinterpret_cast<const float4*>(Rg + L.lambda + 4 * pair_index(a, b));
+    if (prm.warm_start && ((w >> 25) & 3)) {   // the impulses it accumulated: still in this lane, or in the HBM record
+      if (((w >> 18) & 127) == kept_id) lam = kept_lam;
+      else lam = *reinterpret_cast<const float4*>(Rg + L.lambda + 4 * pair_index(a, b));
+    }
     presolve(E, prm, m, w, lam, o.rc, o.ima, o.iia, o.imb, o.iib);
     o.pa = a; o.pb = b;
     o.sa = ((fixed >> a) & 1u) ? K::X_DUMP - L.vel_x : a;
@@ -857,6 +859,13 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
   int n_clevels = 0;          // next free level of this lane's shape
   int wave_clevels = 0;       // levels of the wavefront's deepest environment
   bool levels_valid = false;  // false until the levels of the current set of colliding pairs are worked out
+  // Likewise the list of candidate pairs (it stays in LDS) while no lane's candidates change, and the
+  // accumulated impulses of the pairs a lane kept in registers (A.7): if the lane keeps the same pair in the
+  // next substep they are taken from here, not from the HBM record.
+  unsigned prev_cand = 0u, kind_tot = 0u;
+  bool list_valid = false;
+  int kept_id = -1;           // (the first of the lane's two pairs only: a second one is rare)
+  float4 kept_lam = make_float4(0.f, 0.f, 0.f, 0.f);
   unsigned* rmask = reinterpret_cast<unsigned*>(E + K::X_RMASK);
   unsigned char* lvl = reinterpret_cast<unsigned char*>(E + K::X_LVL);
   float* pool = E + K::X_POOL;
@@ -1012,18 +1021,22 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       if (k < 4) bitmap[k] = 0u;
       rmask[k] = 0u;
       int kind_n[3], kind_off[3];
-      {
+      const bool same_list = list_valid && !__any(cand != prev_cand);
+      prev_cand = cand;
+      list_valid = true;
+      if (!same_list) {
         const unsigned m0 = cand & pp_mask, m1 = cand & pc_mask, m2 = cand & ~(pp_mask | pc_mask);
         const unsigned mine = (unsigned)__popc(m0) | ((unsigned)__popc(m1) << 8) | ((unsigned)__popc(m2) << 16);
-        const unsigned incl = group_prefix_sum(mine), tot = group_sum(mine), excl = incl - mine;
-        kind_n[0] = tot & 255; kind_n[1] = (tot >> 8) & 255; kind_n[2] = (tot >> 16) & 255;
-        kind_off[0] = 0; kind_off[1] = kind_n[0]; kind_off[2] = kind_n[0] + kind_n[1];
-        int w0 = kind_off[0] + (int)(excl & 255), w1 = kind_off[1] + (int)((excl >> 8) & 255);
-        int w2 = kind_off[2] + (int)((excl >> 16) & 255);
+        const unsigned incl = group_prefix_sum(mine), excl = incl - mine;
+        kind_tot = group_sum(mine);
+        int w0 = (int)(excl & 255), w1 = (int)(kind_tot & 255) + (int)((excl >> 8) & 255);
+        int w2 = (int)(kind_tot & 255) + (int)((kind_tot >> 8) & 255) + (int)((excl >> 16) & 255);
         for (unsigned mm = m0; mm != 0u; mm &= mm - 1u) cand_list[w0++] = (unsigned char)((__ffs(mm) - 1) * GP + kp);
         for (unsigned mm = m1; mm != 0u; mm &= mm - 1u) cand_list[w1++] = (unsigned char)((__ffs(mm) - 1) * GP + kp);
         for (unsigned mm = m2; mm != 0u; mm &= mm - 1u) cand_list[w2++] = (unsigned char)((__ffs(mm) - 1) * GP + kp);
       }
+      kind_n[0] = kind_tot & 255; kind_n[1] = (kind_tot >> 8) & 255; kind_n[2] = (kind_tot >> 16) & 255;
+      kind_off[0] = 0; kind_off[1] = kind_n[0]; kind_off[2] = kind_n[0] + kind_n[1];
       wave_sync();
       K2D_T(kT_Cull);
       int pool_base = 0;
@@ -1087,9 +1100,9 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       typename S::Own oa, ob;
       oa.id = -1; ob.id = -1; oa.lv = -1; ob.lv = -1;
       oa.rc.ab = 0; ob.rc.ab = 0;
-      if (k < pool_base) S::take_own(E, Rg, prm, k, static_mask, oa);
+      if (k < pool_base) S::take_own(E, Rg, prm, k, static_mask, kept_id, kept_lam, oa);
       if (__any(pool_base > G)) {
-        if (k + G < pool_base && k + G < K::NREG) S::take_own(E, Rg, prm, k + G, static_mask, ob);
+        if (k + G < pool_base && k + G < K::NREG) S::take_own(E, Rg, prm, k + G, static_mask, -1, kept_lam, ob);
       }
       wave_sync();
       K2D_T(kT_Presolve);
@@ -1147,6 +1160,13 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       // one level at a time: the pairs held in registers (first and second of the lane), then the listed ones
       const bool any_b = __any(ob.id >= 0);
       auto for_each_level = [&](auto&& f_own, auto&& f_listed) {
+        if (!any_b && !any_listed) {   // the common case, as a loop of its own: one pair per lane, all in registers
+          for (int lv = 0; lv < wave_clevels; ++lv) {
+            if (oa.lv == lv) f_own(oa);
+            wave_sync();
+          }
+          return;
+        }
         for (int lv = 0; lv < wave_clevels; ++lv) {
           if (oa.lv == lv) f_own(oa);
           if (any_b) {
@@ -1381,6 +1401,8 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
                          correct(rp[0], rp[1], rp[3], f2i(rp[4]), make_float4(rp[13], rp[14], rp[23], rp[24]));
                        }
                      });
+      kept_id = oa.id;
+      kept_lam = make_float4(oa.rc.lam_n[0], oa.rc.lam_t[0], oa.rc.lam_n[1], oa.rc.lam_t[1]);
       K2D_T(kT_CorrectPairs);
       for (int lv = 0; lv < wave_levels; ++lv) {
         if (k < J && j_live && j_level == lv) {
