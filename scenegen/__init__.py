@@ -465,6 +465,27 @@ def make_scene(cfg_id, n_envs=None, env_ids=None, episode=0, seed=SEED):
     return caps, params, to_f32(sc)
 
 
+def make_dense_scene(n_envs=None, env_ids=None, episode=0, seed=SEED, pen=(1.6, 3.4)):
+    """The contact-heavy variant of workload 3: the same generator (all 16 shapes active, no rejection,
+    restitution 0, friction U[0.2, 1]), but the two static walls stand at the edges of a pen only
+    `pen[1] - pen[0]` wide, so that the heap cannot spread over the floor and piles up in layers.  What it
+    yields (oracle counters): about 14 colliding pairs per environment once settled, up to 21, more than 16
+    in a tenth of the environment-steps -- thirteen movable convex shapes in the plane do not touch more
+    neighbours than that once they rest.  Returns (caps, params, scene) like make_scene."""
+    cfg = CONFIGS[3]
+    caps = CAPS[cfg["size"]]
+    if env_ids is None:
+        env_ids = np.arange(8192 if n_envs is None else n_envs)
+    xl, xr = pen
+    walls = [(xl - 0.1, 5.0, 0.1, 5.0), (xr + 0.1, 5.0, 0.1, 5.0)]
+    sc = _generate(3, caps, np.asarray(env_ids), episode, seed ^ 0x00D0E05E, statics=[_FLOOR] + walls, poly_kind="hull",
+                   extent=(0.3, 1.0), circle_r=(0.05, 0.5), region=((xl + 0.3, xr - 0.3), (1.0, 4.0)), retries=0,
+                   joint_fixed_pattern=[0, 0, 1, 0, 0, 1], mask_mode="none", restitution_hi=0.0,
+                   friction_range=(0.2, 1.0))
+    sc.pop("size_class", None)
+    return caps, default_params(cfg["n_substeps"], cfg["n_iters"]), to_f32(sc)
+
+
 def make_stack_scene(n_envs=None, env_ids=None, episode=0, seed=SEED, n_substeps=3, n_iters=10):
     """A stacking workload (the case Appendix A.7 describes: rectangles resting on top of each other, where
     solving one contact disturbs its neighbours): L capacities, the floor and two walls, nine boxes piled

@@ -76,6 +76,20 @@ def test_stacking_workload_bit_identical():
     assert ((os_["pair_count"] > 0).sum(1) == 13).all()
 
 
+def test_dense_pile_workload_bit_identical():
+    """Workload 3's heap in a narrow pen: many environments keep more colliding pairs than one per lane, so the
+    second register-held pair of a lane is exercised over several wavefronts."""
+    caps, prm, sc = scenegen.make_dense_scene(n_envs=195)
+    act = scenegen.make_actions(3, 96, 195)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b = parity.run_gpu(caps, prm, sc, act)
+    gs, os_ = b.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    n_pairs = (os_["pair_count"] > 0).sum(1)
+    assert (n_pairs > 16).sum() >= 8 and n_pairs.mean() > 10
+
+
 @pytest.mark.parametrize("cfg,B,n,steps", [(0, 16, 67, 120), (0, 1, 67, 60), (0, 32, 131, 60), (1, 16, 131, 64),
                                            (1, 5, 67, 48), (2, 16, 259, 64), (2, 1, 131, 32), (2, 32, 131, 48),
                                            (3, 16, 131, 64), (3, 7, 67, 48), (4, 16, 195, 48)])
