@@ -157,8 +157,8 @@ struct Cfg {
   static constexpr int X_SCHED = X_LIST + LIST_W;          // bytes [R][LCAP]: numbers of the active pairs not held in registers, level by level
   static constexpr int X_PSTATE = align_up(X_SCHED + R * LCAP / 4, 4);   // bytes [G][16]: active-point bits of pair (r, k) at [k][r]
   static constexpr int X_BITMAP = X_PSTATE + GP * 4;       // 4 words: bit id set = pair id is active and not held in registers
-  static constexpr int X_RMASK = X_BITMAP + 4;             // [G] words: bit r set = the shape has an active pair in round r
-  static constexpr int X_LVL = X_RMASK + G;                // bytes [NID]: dependency level of pair id
+  static constexpr int X_NEXT = X_BITMAP + 4;              // bytes [N]: next free dependency level of every shape
+  static constexpr int X_LVL = X_NEXT + (N + 3) / 4;       // bytes [NID]: dependency level of pair id
   static constexpr int X_STAGE = X_LVL + (NID + 3) / 4;    // staged manifolds, kManW words each
   static constexpr int X_DUMP = X_STAGE;                   // (once the staged manifolds are taken) 2N+1 words that swallow the
                                                            // velocity stores of shapes no impulse moves (offsets 0, N, 2N)
@@ -817,11 +817,11 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
   if (k < GP && first)
     for (int r = 0; r < 16; ++r) pstate[k * 16 + r] = 0;
   wave_sync();
-  unsigned long long my_ab = 0ull;   // this lane's pairs, a | b << 4, eight bits for each of its rounds
+  unsigned my_ab4[4] = {0u, 0u, 0u, 0u};   // this lane's pairs, a | b << 4, eight bits for each of its rounds
   for (int r = 0; r < R; ++r) {
     int a, b;
     if (((my_r >> r) & 1u) && S::sched_pair(r, kp, a, b)) {
-      my_ab |= (unsigned long long)(a | (b << 4)) << (8 * (r / H));
+      my_ab4[(r / H) >> 2] |= (unsigned)(a | (b << 4)) << (8 * ((r / H) & 3));
       if (b < P) pp_mask |= 1u << r;
       else if (a < P) pc_mask |= 1u << r;
       bool ok = (f2i(E[L.shape_flags + a]) & 1) && (f2i(E[L.shape_flags + b]) & 1) &&
@@ -836,27 +836,8 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
     }
   }
   wave_sync();   // the joined-shape words share their LDS with the candidate list
-  // Lane s of the group also stands for shape s when dependency levels are worked out: for every round,
-  // its partner, the pair's slot in the round and whether the pair exists, eight bits per round.
-  unsigned rp[4] = {0u, 0u, 0u, 0u};
-  for (int r = 0; r < R; ++r) {
-    constexpr int M1 = K::M - 1;
-    int partner, ks;
-    if (k == M1) { partner = r; ks = 0; }
-    else if (k == r) { partner = M1; ks = 0; }
-    else {
-      int d = k - r; if (d < 0) d += M1;
-      if (d <= K::PPR - 1) { ks = d; partner = r - d; if (partner < 0) partner += M1; }
-      else { ks = M1 - d; partner = r + ks; if (partner >= M1) partner -= M1; }
-    }
-    const bool ok = k < N && partner < N;
-    const unsigned e = ok ? (unsigned)(partner | (ks << 4) | 0x80) : (unsigned)(k & (G - 1));   // no pair: look at oneself
-    rp[r >> 2] |= e << (8 * (r & 3));
-  }
-  const bool movable = k < N && !((static_mask >> k) & 1u);
   // Dependency levels of the collision constraints are kept from one substep to the next: they depend
   // only on which pairs collide, and that set is the same in most consecutive substeps.
-  int n_clevels = 0;          // next free level of this lane's shape
   int wave_clevels = 0;       // levels of the wavefront's deepest environment
   bool levels_valid = false;  // false until the levels of the current set of colliding pairs are worked out
   // Likewise the list of candidate pairs (it stays in LDS) while no lane's candidates change, and the
@@ -866,7 +847,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
   bool list_valid = false;
   int kept_id = -1;           // (the first of the lane's two pairs only: a second one is rare)
   float4 kept_lam = make_float4(0.f, 0.f, 0.f, 0.f);
-  unsigned* rmask = reinterpret_cast<unsigned*>(E + K::X_RMASK);
+  unsigned char* next_free = reinterpret_cast<unsigned char*>(E + K::X_NEXT);
   unsigned char* lvl = reinterpret_cast<unsigned char*>(E + K::X_LVL);
   float* pool = E + K::X_POOL;
   float* spill = Rg + K::G_SPILL;
@@ -995,10 +976,9 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       unsigned cand = 0u;
       bool set_changed = false;   // a pair of this lane collides now and did not one substep ago, or the reverse
       {
-        const unsigned ab_lo = (unsigned)my_ab, ab_hi = (unsigned)(my_ab >> 32);
 #pragma unroll
         for (int j = 0; j < (R + H - 1) / H; ++j) {   // round j * H + rpar: every lane is busy in every trip
-          const unsigned pk = ((j < 4 ? ab_lo : ab_hi) >> (8 * (j & 3))) & 0xffu;
+          const unsigned pk = (my_ab4[j >> 2] >> (8 * (j & 3))) & 0xffu;
           const int a = pk & 15, b = pk >> 4;
           const float4 ba = *reinterpret_cast<const float4*>(E + K::X_BOX + 4 * a);
           const float4 bb = *reinterpret_cast<const float4*>(E + K::X_BOX + 4 * b);
@@ -1019,7 +999,6 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
         for (unsigned st = gone; st != 0u; st &= st - 1u) pstate[kp * 16 + (__ffs(st) - 1)] = 0;
       }
       if (k < 4) bitmap[k] = 0u;
-      rmask[k] = 0u;
       int kind_n[3], kind_off[3];
       const bool same_list = list_valid && !__any(cand != prev_cand);
       prev_cand = cand;
@@ -1088,8 +1067,6 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
             atomicOr(&bitmap[id >> 5], 1u << (id & 31));
             table[id] = (unsigned char)idx;
           }
-          atomicOr(&rmask[a], 1u << r);
-          atomicOr(&rmask[b], 1u << r);
         }
         if (have) pstate[kk * 16 + r] = (unsigned char)((unsigned)act0 | ((unsigned)act1 << 1));
        }
@@ -1111,29 +1088,36 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       // one level touch disjoint movable shapes and pairs that share one keep their canonical order, so
       // sweeping the levels in order, each level at once, gives the same bits as the sequential sweep --
       // in far fewer trips (everything resting on the static floor is one level; a level never exceeds
-      // the round).  Lane s follows shape s: in every round the two lanes of an active pair exchange the
-      // next free level of their shapes and both move on to one past the larger.
+      // the round).  The lane that tests a pair also places it: the pairs of a round touch disjoint
+      // shapes, so the lanes of a round read and advance the next free level of their two shapes
+      // (bytes in LDS) without getting in each other's way, and the rounds follow one another.
       if (!levels_valid || __any(set_changed)) {
-        n_clevels = 0;
-        const unsigned rm = rmask[k];
+        if (k < (N + 3) / 4) reinterpret_cast<unsigned*>(next_free)[k] = 0u;
+        wave_sync();
+        const uint4 ps = *reinterpret_cast<const uint4*>(pstate + kp * 16);
+        int my_levels = 0;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          const unsigned e = (rp[r >> 2] >> (8 * (r & 3))) & 0xffu;
-          const bool act = (rm >> r) & 1u;
+          const unsigned w = r < 4 ? ps.x : r < 8 ? ps.y : r < 12 ? ps.z : ps.w;
+          const bool act = ((my_r >> r) & 1u) && ((w >> (8 * (r & 3))) & 0xffu) != 0u;
           if (__any(act)) {
-            const int partner = e & 15;
-            const int mine = movable ? n_clevels : 0;
-            const int other = __shfl(mine, partner, G);
-            const int lv = max(mine, other);
             if (act) {
-              if (movable) n_clevels = lv + 1;
-              if (k < partner) lvl[r * GP + ((e >> 4) & 7)] = (unsigned char)lv;
+              const unsigned pk = (my_ab4[(r / H) >> 2] >> (8 * ((r / H) & 3))) & 0xffu;
+              const int a = pk & 15, b = pk >> 4;
+              const bool ma = !((static_mask >> a) & 1u), mb = !((static_mask >> b) & 1u);
+              const int la = ma ? (int)next_free[a] : 0, lb = mb ? (int)next_free[b] : 0;
+              const int lv = max(la, lb);
+              if (ma) next_free[a] = (unsigned char)(lv + 1);
+              if (mb) next_free[b] = (unsigned char)(lv + 1);
+              lvl[r * GP + kp] = (unsigned char)lv;
+              my_levels = max(my_levels, lv + 1);
             }
+            wave_sync();
           }
         }
         wave_clevels = 0;
         for (int lv = 1; lv <= R; ++lv)
-          if (__any(n_clevels >= lv)) wave_clevels = lv;
+          if (__any(my_levels >= lv)) wave_clevels = lv;
         levels_valid = true;
       }
       wave_sync();
@@ -1317,7 +1301,7 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
             pm = group_or(pm);
             wave_sync();
             if (__any(pm != 0u)) {
-              if (movable && pm != 0u) {
+              if (k < N && !((static_mask >> k) & 1u) && pm != 0u) {
                 float vx = E[L.vel_x + k], vy = E[L.vel_y + k], w = E[L.omega + k];
                 const float im = E[L.inv_mass + k], ii = E[L.inv_inertia + k];
                 for (unsigned m = pm; m != 0u; m &= m - 1u) {
