@@ -112,6 +112,14 @@ size_t k2d_state_bytes(const k2d_caps* caps, int n_envs);
 int k2d_alloc_batch(const k2d_caps* caps, const k2d_params* params, int n_envs, void* state_dev,
                     size_t state_bytes, k2d_batch** out);
 
+/* How the step kernel maps environments onto the 64 lanes of a wavefront: `lanes` = 16 (four environments
+ * per wavefront), 8 (eight per wavefront: half the instructions per environment, twice the on-chip memory
+ * per wavefront), or 0 = chosen per launch (the default: 8 lanes for Small environments in batches of more
+ * than 8192, where that is faster, 16 otherwise).  The mapping changes no result (the pairs of a round of
+ * the canonical order touch disjoint shapes, A.8, whichever lanes hold them).  With 8 lanes the batched
+ * schedule takes batch sizes up to 16 (the paper's).  K2D_E_ARG otherwise. */
+int k2d_set_lanes_per_env(k2d_batch* batch, int lanes);
+
 /* Frees the host descriptor only. */
 int k2d_free_batch(k2d_batch* batch);
 

@@ -58,6 +58,7 @@ def _declare(L):
     L.k2d_alloc_batch.argtypes = [ctypes.POINTER(k2d_caps), ctypes.POINTER(k2d_params), i32, vp, ctypes.c_size_t,
                                   ctypes.POINTER(vp)]
     L.k2d_free_batch.argtypes = [vp]
+    L.k2d_set_lanes_per_env.argtypes = [vp, i32]
     L.k2d_reset.argtypes = [vp, vp, vp, i32, vp]
     L.k2d_step.argtypes = [vp, vp, i32, i32, vp]
     L.k2d_step_noalloc.argtypes = [vp, vp, i32, i32, vp]
@@ -89,7 +90,7 @@ def use_library(path):
     return _lib
 
 
-EXPORTS = ["k2d_get_layout", "k2d_obs_dim", "k2d_state_bytes", "k2d_alloc_batch", "k2d_free_batch", "k2d_reset", "k2d_step",
+EXPORTS = ["k2d_get_layout", "k2d_obs_dim", "k2d_state_bytes", "k2d_alloc_batch", "k2d_set_lanes_per_env", "k2d_free_batch", "k2d_reset", "k2d_step",
            "k2d_step_noalloc", "k2d_step_reset", "k2d_read_outcome", "k2d_read_entities", "k2d_decode_actions",
            "k2d_read_obs", "k2d_read_contacts", "k2d_read_health", "k2d_read_state", "k2d_write_state"]
 
@@ -235,6 +236,10 @@ class Batch:
         c, p = make_caps(self.caps), make_params(params)
         _check(lib().k2d_alloc_batch(ctypes.byref(c), ctypes.byref(p), self.n_envs, self.state.data_ptr(), nbytes,
                                      ctypes.byref(self._h)), "k2d_alloc_batch")
+
+    def set_lanes_per_env(self, lanes):
+        """Lane mapping of the step kernel: 8 or 16 lanes per environment, 0 = chosen by the batch size."""
+        _check(lib().k2d_set_lanes_per_env(self._h, int(lanes)), "k2d_set_lanes_per_env")
 
     def __del__(self):
         if getattr(self, "_h", None) and self._h.value:

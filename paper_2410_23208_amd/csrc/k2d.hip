@@ -126,18 +126,19 @@ struct Cfg {
   static constexpr int G = GP * H;             // lanes per environment: lane k tests pair k % GP of the rounds
                                                // r with r % H == k / GP
   static constexpr int EPW = 64 / G;           // environments per wavefront
-  static_assert(PPR <= 8 && J <= G && T <= G && R <= 15 && G == 16 && (H & (H - 1)) == 0 && (R + H - 1) / H <= 8,
+  static_assert(PPR <= 8 && J <= G && T <= G && R <= 15 && (G == 8 || G == 16) && (H & (H - 1)) == 0 &&
+                    (R + H - 1) / H <= 16,
                 "capacity class does not fit the lane mapping");
   // Active pairs are numbered 0, 1, ... as the narrowphase finds them.  Pairs below NREG live in
   // registers (lane k holds pairs k and G + k): the lane that found the manifold leaves it in an LDS
   // staging slot, the lane that keeps the pair derives the substep constants from it.  Pairs beyond them
-  // live as full records in a small LDS pool (POOL records) or, past that, in the HBM record.
+  // live as full records in a small LDS pool (POOL records, as many as the LDS budget of the class has
+  // room for, eight at most) or, past that, in the HBM record.
   static constexpr int NREG = 2 * G, kManW = 9;
-  static constexpr int POOL = (NP > NREG && NP - NREG <= 4) ? NP - NREG : 0;   // (a class with few pairs beyond the
-                                                                               // registers keeps them all in LDS)
   static constexpr k2d_layout L = make_layout(P, C, J, T);
-  // HBM record: state words, then room for the pair records that do not fit the LDS pool
-  static constexpr int SPILL = (NP > NREG + POOL ? NP - NREG - POOL : 0);
+  // HBM record: state words, then room for the pair records that neither registers nor the LDS pool hold
+  // (sized for the lane mapping that holds fewest, so that every mapping of a class shares one record)
+  static constexpr int SPILL = NP > 16 ? NP - 16 : 0;
   static constexpr int G_SPILL = align_up(L.state_words, 4);
   static constexpr int REC_WORDS = align_up(G_SPILL + SPILL * kRecW, 32);
   // LDS image of one environment: scene words, then derived data
@@ -164,10 +165,17 @@ struct Cfg {
                                                            // velocity stores of shapes no impulse moves (offsets 0, N, 2N)
   static constexpr int X_POOL = X_STAGE + NREG * kManW;
   static_assert(NREG * kManW >= 2 * N + 1 && L.pos_x == 0 && L.pos_y == N, "dump slots do not fit the staging area");
+  // LDS budget of one environment: a CU's 160 KiB shared by the lanes of eight wavefronts' worth of
+  // 16-lane environments (or four wavefronts' worth of 8-lane ones): 1280 words.  The stride is an odd
+  // multiple of G words, so that the same word of different environments falls into different banks.
+  static constexpr int MAX_STRIDE = (1280 / G - ((1280 / G) % 2 == 0 ? 1 : 0)) * G;
+  static constexpr int POOL_WANT = NP > NREG ? (NP - NREG < 8 ? NP - NREG : 8) : 0;
+  static constexpr int POOL_FIT = MAX_STRIDE > X_POOL ? (MAX_STRIDE - X_POOL) / kRecW : 0;
+  static constexpr int POOL = POOL_WANT < POOL_FIT ? POOL_WANT : POOL_FIT;
+  static_assert(NREG + POOL >= 16 && NP - NREG - POOL <= SPILL, "spill room of the record");
   static constexpr int LDS_WORDS = X_POOL + POOL * kRecW;
-  // stride = odd multiple of G words: the same word of different environments falls into different banks
   static constexpr int LDS_STRIDE = align_up(LDS_WORDS - G, 2 * G) + G;
-  static_assert(LDS_STRIDE >= LDS_WORDS && (LDS_STRIDE / G) % 2 == 1, "stride rule");
+  static_assert(LDS_STRIDE >= LDS_WORDS && (LDS_STRIDE / G) % 2 == 1 && LDS_STRIDE <= MAX_STRIDE, "stride rule");
   static constexpr int LDS_BYTES = LDS_STRIDE * EPW * 4;
 };
 
@@ -182,28 +190,51 @@ struct Params {   // device copy of k2d_params with the substep precomputed
 
 __device__ __forceinline__ int f2i(float f) { return __float_as_int(f); }
 
-// Inclusive prefix sum and sum over the 16 lanes of an environment's group (one DPP row: shifts within the
-// row read zero where there is no source lane; rotations reach every lane).
-__device__ __forceinline__ unsigned group_prefix_sum(unsigned v) {
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);
+// Inclusive prefix sum, sum and OR over the G lanes of an environment's group.  A group of 16 is one DPP
+// row (shifts within the row read zero where there is no source lane; rotations reach every lane); a
+// group of 8 is half a row: shifts are masked at the group's edge, sums and ORs use the exchanges within
+// a quad and the mirror of the half row.
+#define K2D_DPP(v, ctrl, bc) __builtin_amdgcn_update_dpp(0, (int)(v), ctrl, 0xf, 0xf, bc)
+template <int G>
+__device__ __forceinline__ unsigned group_prefix_sum(unsigned v, int k) {
+  if constexpr (G == 16) {
+    v += (unsigned)K2D_DPP(v, 0x111, true);
+    v += (unsigned)K2D_DPP(v, 0x112, true);
+    v += (unsigned)K2D_DPP(v, 0x114, true);
+    v += (unsigned)K2D_DPP(v, 0x118, true);
+  } else {
+    unsigned t = (unsigned)K2D_DPP(v, 0x111, true); v += (k >= 1) ? t : 0u;
+    t = (unsigned)K2D_DPP(v, 0x112, true); v += (k >= 2) ? t : 0u;
+    t = (unsigned)K2D_DPP(v, 0x114, true); v += (k >= 4) ? t : 0u;
+  }
   return v;
 }
+template <int G>
 __device__ __forceinline__ unsigned group_sum(unsigned v) {
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x121, 0xf, 0xf, false);
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x122, 0xf, 0xf, false);
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x124, 0xf, 0xf, false);
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xf, 0xf, false);
+  if constexpr (G == 16) {
+    v += (unsigned)K2D_DPP(v, 0x121, false);
+    v += (unsigned)K2D_DPP(v, 0x122, false);
+    v += (unsigned)K2D_DPP(v, 0x124, false);
+    v += (unsigned)K2D_DPP(v, 0x128, false);
+  } else {
+    v += (unsigned)K2D_DPP(v, 0xB1, false);    // lanes 0<->1, 2<->3 of every quad
+    v += (unsigned)K2D_DPP(v, 0x4E, false);    // lanes 0<->2, 1<->3
+    v += (unsigned)K2D_DPP(v, 0x141, false);   // mirror of the half row: the other quad's sum
+  }
   return v;
 }
-// OR over the 16 lanes of an environment's group (one DPP row: rotations by 1, 2, 4, 8 within the row).
+template <int G>
 __device__ __forceinline__ unsigned group_or(unsigned v) {
-  v |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x121, 0xf, 0xf, false);
-  v |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x122, 0xf, 0xf, false);
-  v |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x124, 0xf, 0xf, false);
-  v |= (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xf, 0xf, false);
+  if constexpr (G == 16) {
+    v |= (unsigned)K2D_DPP(v, 0x121, false);
+    v |= (unsigned)K2D_DPP(v, 0x122, false);
+    v |= (unsigned)K2D_DPP(v, 0x124, false);
+    v |= (unsigned)K2D_DPP(v, 0x128, false);
+  } else {
+    v |= (unsigned)K2D_DPP(v, 0xB1, false);
+    v |= (unsigned)K2D_DPP(v, 0x4E, false);
+    v |= (unsigned)K2D_DPP(v, 0x141, false);
+  }
   return v;
 }
 
@@ -672,7 +703,7 @@ struct Step {
 // record l of `levels` (what k2d_reset does between launches, without leaving the kernel).
 // BATCHED: the collision constraints of a sweep are solved in the batches of A.8 instead of level by level.
 template <class K, bool RESET, bool BATCHED>
-__global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ state, const float* __restrict__ actions,
+__global__ void __launch_bounds__(64, K::EPW == 4 ? 2 : 1) k2d_step_kernel(float* __restrict__ state, const float* __restrict__ actions,
                                                       int n_envs, int n_steps, Params prm,
                                                       const float* __restrict__ levels, int n_level_records,
                                                       const int32_t* __restrict__ reset_level,
@@ -1006,8 +1037,8 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
       if (!same_list) {
         const unsigned m0 = cand & pp_mask, m1 = cand & pc_mask, m2 = cand & ~(pp_mask | pc_mask);
         const unsigned mine = (unsigned)__popc(m0) | ((unsigned)__popc(m1) << 8) | ((unsigned)__popc(m2) << 16);
-        const unsigned incl = group_prefix_sum(mine), excl = incl - mine;
-        kind_tot = group_sum(mine);
+        const unsigned incl = group_prefix_sum<G>(mine, k), excl = incl - mine;
+        kind_tot = group_sum<G>(mine);
         int w0 = (int)(excl & 255), w1 = (int)(kind_tot & 255) + (int)((excl >> 8) & 255);
         int w2 = (int)(kind_tot & 255) + (int)((kind_tot >> 8) & 255) + (int)((excl >> 16) & 255);
         for (unsigned mm = m0; mm != 0u; mm &= mm - 1u) cand_list[w0++] = (unsigned char)((__ffs(mm) - 1) * GP + kp);
@@ -1298,24 +1329,26 @@ __global__ void __launch_bounds__(64, 2) k2d_step_kernel(float* __restrict__ sta
                 }
               }
             }
-            pm = group_or(pm);
+            pm = group_or<G>(pm);
             wave_sync();
             if (__any(pm != 0u)) {
-              if (k < N && !((static_mask >> k) & 1u) && pm != 0u) {
-                float vx = E[L.vel_x + k], vy = E[L.vel_y + k], w = E[L.omega + k];
-                const float im = E[L.inv_mass + k], ii = E[L.inv_inertia + k];
-                for (unsigned m = pm; m != 0u; m &= m - 1u) {
-                  LdsCF p = (LdsCF)(E + K::X_STAGE + (__ffs(m) - 1) * K::kManW);
-                  const int ab = f2i(p[8]);
-                  if ((ab & 0xff) == k) {
-                    apply_impulse(vx, vy, w, im, ii, p[0], p[1], p[4], p[5]);
-                    apply_impulse(vx, vy, w, im, ii, p[2], p[3], p[4], p[5]);
-                  } else if ((ab >> 8) == k) {
-                    apply_impulse(vx, vy, w, im, ii, -p[0], -p[1], p[6], p[7]);
-                    apply_impulse(vx, vy, w, im, ii, -p[2], -p[3], p[6], p[7]);
+              for (int i = k; i < N; i += G) {   // lane k applies to shapes k, k + G, ...
+                if (!((static_mask >> i) & 1u) && pm != 0u) {
+                  float vx = E[L.vel_x + i], vy = E[L.vel_y + i], w = E[L.omega + i];
+                  const float im = E[L.inv_mass + i], ii = E[L.inv_inertia + i];
+                  for (unsigned m = pm; m != 0u; m &= m - 1u) {
+                    LdsCF p = (LdsCF)(E + K::X_STAGE + (__ffs(m) - 1) * K::kManW);
+                    const int ab = f2i(p[8]);
+                    if ((ab & 0xff) == i) {
+                      apply_impulse(vx, vy, w, im, ii, p[0], p[1], p[4], p[5]);
+                      apply_impulse(vx, vy, w, im, ii, p[2], p[3], p[4], p[5]);
+                    } else if ((ab >> 8) == i) {
+                      apply_impulse(vx, vy, w, im, ii, -p[0], -p[1], p[6], p[7]);
+                      apply_impulse(vx, vy, w, im, ii, -p[2], -p[3], p[6], p[7]);
+                    }
                   }
+                  E[L.vel_x + i] = vx; E[L.vel_y + i] = vy; E[L.omega + i] = w;
                 }
-                E[L.vel_x + k] = vx; E[L.vel_y + k] = vy; E[L.omega + k] = w;
               }
               wave_sync();
             }
@@ -1807,14 +1840,22 @@ __global__ void __launch_bounds__(64) k2d_health_kernel(const float* state, uint
 // ---------------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------------
-#ifndef K2D_H_L
-#define K2D_H_L 2
-#endif
+// Two lane mappings per capacity class: 16 lanes per environment (four environments per wavefront) and 8
+// lanes per environment (eight per wavefront: half the instructions per environment, but an LDS image twice
+// as large per wavefront).
 using CfgS = Cfg<5, 2, 1, 1, 4>;
 using CfgM = Cfg<6, 3, 2, 2, 2>;
-using CfgL = Cfg<12, 4, 6, 2, K2D_H_L>;
-// four L wavefronts must share one CU's 160 KiB of LDS: with 8192 environments every SIMD then holds one
-static_assert(CfgL::LDS_BYTES * CfgL::G <= 40960 * 8, "L image too large: every SIMD must be able to hold 16 L environments' worth of lanes");
+using CfgL = Cfg<12, 4, 6, 2, 2>;
+using CfgS8 = Cfg<5, 2, 1, 1, 2>;
+using CfgM8 = Cfg<6, 3, 2, 2, 1>;
+using CfgL8 = Cfg<12, 4, 6, 2, 1>;
+static_assert(CfgS::G == 16 && CfgM::G == 16 && CfgL::G == 16 && CfgS8::G == 8 && CfgM8::G == 8 && CfgL8::G == 8, "lane mappings");
+static_assert(CfgS::REC_WORDS == CfgS8::REC_WORDS && CfgM::REC_WORDS == CfgM8::REC_WORDS &&
+                  CfgL::REC_WORDS == CfgL8::REC_WORDS, "the mappings of a class share one record");
+// the LDS images of a CU's resident wavefronts must fit its 160 KiB: eight (16 lanes) or four (8 lanes) per CU
+static_assert(CfgL::LDS_BYTES * 8 <= 160 * 1024 && CfgL8::LDS_BYTES * 4 <= 160 * 1024, "L image too large");
+// environments beyond which the 8-lane mapping is chosen: what the 16-lane mapping keeps resident at once
+constexpr int kResidentEnvs16 = 256 * 8 * 4;
 
 int caps_class(const k2d_caps* c) {
   if (!c) return -1;
@@ -1832,7 +1873,7 @@ std::mutex g_host_mutex;
 // Ordering scratch of k2d_step_noalloc: slot -> environment for one launch, then the sort keys.  One copy
 // per GPU, inside the code object, held until the process ends.  In host code the array's name is only a
 // handle for hipGetSymbolAddress; kernels get the address that call returns.
-constexpr int kNoAllocSlots = (K2D_NOALLOC_MAX_ENVS + 3) / 4 * 4;
+constexpr int kNoAllocSlots = (K2D_NOALLOC_MAX_ENVS + 7) / 8 * 8;
 __device__ __align__(256) int32_t scratch[2 * kNoAllocSlots];
 int32_t* g_scratch_ptr[kMaxDevices] = {};
 
@@ -1905,6 +1946,7 @@ struct k2d_batch {
   int rec_words;
   float* state;
   int32_t* order;   // behind the records in the caller's buffer: slot -> environment for one launch
+  int lanes;        // lanes per environment of the step kernel: 8, 16, or 0 = chosen by the batch size
 };
 
 // launches of fewer steps than this keep the identity ordering (the ordering pass would cost more than it saves)
@@ -1937,11 +1979,30 @@ static int step_launch_as(k2d_batch* b, const float* actions_dev, int n_envs, in
     if (prm.n_batches < 2) return K2D_E_ARG;   // (the kernel relies on the two points of a pair being in different batches)
   }
   int32_t* ord = n_steps >= kOrderMinSteps ? order_buf : nullptr;
-  switch (b->cls) {
-    case 0: return launch_step<CfgS, RESET, BATCHED>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
-    case 1: return launch_step<CfgM, RESET, BATCHED>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
-    default: return launch_step<CfgL, RESET, BATCHED>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, b->rec_words, b->layout, st);
+  // lane mapping: as set on the batch; else 16 lanes per environment, except for Small environments in
+  // batches larger than that mapping keeps resident at once.  (Measured on MI355X: with 8 lanes the Small
+  // class steps 16384 and more environments 1.5 to 1.7 times faster; the Medium and Large classes are
+  // slower with 8 lanes at every batch size -- their LDS images allow one wavefront of eight environments per
+  // SIMD, whose dependent instructions then have no second wavefront to overlap with.)
+  int lanes = b->lanes;
+  if (lanes == 0) lanes = (b->cls == 0 && n_envs > kResidentEnvs16 && !(BATCHED && b->params.batch_size > 16)) ? 8 : 16;
+  if (lanes == 8 && BATCHED && b->params.batch_size > 16) return K2D_E_ARG;
+#define K2D_STEP_AS(CFG) \
+  launch_step<CFG, RESET, BATCHED>(b->state, actions_dev, n_envs, n_steps, prm, lv, n_levels, reset_level_dev, ord, \
+                                   b->rec_words, b->layout, st)
+  if (lanes == 8) {
+    switch (b->cls) {
+      case 0: return K2D_STEP_AS(CfgS8);
+      case 1: return K2D_STEP_AS(CfgM8);
+      default: return K2D_STEP_AS(CfgL8);
+    }
   }
+  switch (b->cls) {
+    case 0: return K2D_STEP_AS(CfgS);
+    case 1: return K2D_STEP_AS(CfgM);
+    default: return K2D_STEP_AS(CfgL);
+  }
+#undef K2D_STEP_AS
 }
 template <bool RESET>
 static int step_launch(k2d_batch* b, const float* actions_dev, int n_envs, int n_steps, const float* lv, int n_levels,
@@ -1979,7 +2040,7 @@ int k2d_obs_dim(const k2d_caps* caps) {
 size_t k2d_state_bytes(const k2d_caps* caps, int n_envs) {
   int cls = caps_class(caps);
   if (cls < 0 || n_envs < 1) return 0;
-  return records_bytes(cls, n_envs) + 2 * (size_t)((n_envs + 3) / 4 * 4) * sizeof(int32_t);   // + ordering, keys
+  return records_bytes(cls, n_envs) + 2 * (size_t)((n_envs + 7) / 8 * 8) * sizeof(int32_t);   // + ordering, keys
 }
 
 int k2d_alloc_batch(const k2d_caps* caps, const k2d_params* params, int n_envs, void* state_dev, size_t state_bytes,
@@ -2001,11 +2062,19 @@ int k2d_alloc_batch(const k2d_caps* caps, const k2d_params* params, int n_envs, 
   b->rec_words = rec_words_of(cls);
   b->state = static_cast<float*>(state_dev);
   b->order = reinterpret_cast<int32_t*>(static_cast<char*>(state_dev) + records_bytes(cls, n_envs));
+  b->lanes = 0;
   {   // set-up for k2d_step_noalloc on this device (nothing to do, and no error, where no GPU is visible)
     int32_t* unused = nullptr;
     (void)scratch_of_current_device(&unused);
   }
   *out = b;
+  return K2D_OK;
+}
+
+int k2d_set_lanes_per_env(k2d_batch* b, int lanes) {
+  if (!b || (lanes != 0 && lanes != 8 && lanes != 16)) return K2D_E_ARG;
+  if (lanes == 8 && b->params.batch_size > 16) return K2D_E_ARG;
+  b->lanes = lanes;
   return K2D_OK;
 }
 

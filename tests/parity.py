@@ -17,11 +17,13 @@ def run_oracle(caps, params, scene, actions, dtype="f32", n_threads=8):
     return o
 
 
-def run_gpu(caps, params, scene, actions, chunk=None):
+def run_gpu(caps, params, scene, actions, chunk=None, lanes=0):
     import torch
     import paper_2410_23208_amd as k2d
     n = scene["pos"].shape[0]
     b = k2d.Batch(caps, n, params)
+    if lanes:
+        b.set_lanes_per_env(lanes)        # 8 or 16 lanes per environment instead of the library's own choice
     b.reset(k2d.pack_scenes(caps, scene))
     act = torch.from_numpy(np.ascontiguousarray(actions, dtype=np.float32)).cuda()
     n_steps = act.shape[0]

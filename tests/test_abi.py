@@ -61,6 +61,9 @@ def test_argument_errors_without_device_work():
         prm_b = binding.make_params(dict(scenegen.default_params(), batch_size=bad_b))
         assert lib.k2d_alloc_batch(ctypes.byref(caps), ctypes.byref(prm_b), 4, fake, 1 << 20, ctypes.byref(h)) == -1
     assert lib.k2d_alloc_batch(ctypes.byref(caps), ctypes.byref(prm), 4, fake, 1 << 20, ctypes.byref(h)) == 0
+    assert lib.k2d_set_lanes_per_env(h, 8) == 0 and lib.k2d_set_lanes_per_env(h, 16) == 0
+    assert lib.k2d_set_lanes_per_env(h, 4) == -1 and lib.k2d_set_lanes_per_env(None, 8) == -1
+    assert lib.k2d_set_lanes_per_env(h, 0) == 0
     assert lib.k2d_step(h, None, 4, 1, None) == -1
     assert lib.k2d_step(h, fake, 5, 1, None) == -3
     assert lib.k2d_step(h, fake, 4, 0, None) == -1

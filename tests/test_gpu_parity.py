@@ -64,6 +64,37 @@ def test_bit_identical_other_episodes(cfg, episode, n, steps):
     assert (os_["pair_count"] > 0).sum() > n
 
 
+@pytest.mark.parametrize("cfg,n,steps,B", [(0, 131, 120, 0), (1, 259, 64, 0), (2, 259, 64, 0), (3, 195, 64, 0),
+                                           (4, 259, 48, 0), (2, 131, 32, 16), (0, 67, 40, 5), (1, 131, 32, 1)])
+def test_eight_lanes_per_environment_bit_identical(cfg, n, steps, B):
+    """The other lane mapping of the step kernel (eight environments per wavefront), forced through
+    k2d_set_lanes_per_env: same bits as the oracle on every workload, under both schedules, and the same
+    records as the 16-lane mapping."""
+    caps, prm, sc = scenegen.make_scene(cfg, n_envs=n)
+    prm = dict(prm, batch_size=B)
+    act = scenegen.make_actions(cfg, steps, n)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b8 = parity.run_gpu(caps, prm, sc, act, lanes=8)
+    gs, os_ = b8.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    b16 = parity.run_gpu(caps, prm, sc, act, lanes=16)
+    assert np.array_equal(b8.read_state().cpu().numpy(), b16.read_state().cpu().numpy())
+
+
+def test_eight_lanes_dense_pile_and_pool_overflow():
+    """Many colliding pairs per environment on eight lanes: two register-held pairs per lane, the LDS pool and
+    the records in HBM all take part."""
+    caps, prm, sc = scenegen.make_dense_scene(n_envs=131)
+    act = scenegen.make_actions(3, 64, 131)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b = parity.run_gpu(caps, prm, sc, act, lanes=8)
+    gs, os_ = b.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    assert ((os_["pair_count"] > 0).sum(1) > 16).any()
+
+
 def test_stacking_workload_bit_identical():
     """Towers of up to nine boxes: dependency chains as long as a tower is high."""
     caps, prm, sc = scenegen.make_stack_scene(n_envs=131)
@@ -342,8 +373,8 @@ def test_single_environment_and_empty_scene():
     assert os_["pair_count"].sum() >= 2
 
 
-@pytest.mark.parametrize("B", [0, 16, 32, 3])
-def test_pile_deeper_than_the_lds_pool(B):
+@pytest.mark.parametrize("B,lanes", [(0, 0), (16, 0), (32, 0), (3, 0), (0, 8), (16, 8)])
+def test_pile_deeper_than_the_lds_pool(B, lanes):
     """All 16 shapes of an L scene dumped onto one spot: far more active pairs than the per-environment
     LDS pool holds, so the overflow path through the HBM record is exercised (under both schedules)."""
     caps = scenegen.CAPS["L"]
@@ -359,7 +390,7 @@ def test_pile_deeper_than_the_lds_pool(B):
     sc = sb.scene()
     act = np.zeros((6, 3, caps[2] + caps[3]), dtype=np.float32)
     o = parity.run_oracle(caps, prm, sc, act)
-    b = parity.run_gpu(caps, prm, sc, act)
+    b = parity.run_gpu(caps, prm, sc, act, lanes=lanes)
     gs, os_ = b.state_dict(), o.state()
     assert (os_["pair_count"] > 0).sum(1).max() > 40
     for k in parity.FLOAT_KEYS + parity.INT_KEYS:
