@@ -878,6 +878,13 @@ __global__ void __launch_bounds__(64, K::EPW == 4 ? 2 : 1) k2d_step_kernel(float
   bool list_valid = false;
   int kept_id = -1;           // (the first of the lane's two pairs only: a second one is rare)
   float4 kept_lam = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto flush_kept = [&]() {   // the kept impulses into the HBM record (A.7 state of the environment)
+    if (kept_id >= 0 && env_ok) {
+      int a, b;
+      S::sched_pair(kept_id / GP, kept_id % GP, a, b);
+      *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(a, b)) = kept_lam;
+    }
+  };
   unsigned char* next_free = reinterpret_cast<unsigned char*>(E + K::X_NEXT);
   unsigned char* lvl = reinterpret_cast<unsigned char*>(E + K::X_LVL);
   float* pool = E + K::X_POOL;
@@ -1108,6 +1115,13 @@ __global__ void __launch_bounds__(64, K::EPW == 4 ? 2 : 1) k2d_step_kernel(float
       typename S::Own oa, ob;
       oa.id = -1; ob.id = -1; oa.lv = -1; ob.lv = -1;
       oa.rc.ab = 0; ob.rc.ab = 0;
+      // The pairs change lanes only when the set of colliding pairs changes: then the impulses kept in
+      // registers go to the HBM record first, from where the lanes that take the pairs over read them.
+      if (__any(set_changed)) {
+        flush_kept();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      }
       if (k < pool_base) S::take_own(E, Rg, prm, k, static_mask, kept_id, kept_lam, oa);
       if (__any(pool_base > G)) {
         if (k + G < pool_base && k + G < K::NREG) S::take_own(E, Rg, prm, k + G, static_mask, -1, kept_lam, ob);
@@ -1393,10 +1407,11 @@ __global__ void __launch_bounds__(64, K::EPW == 4 ? 2 : 1) k2d_step_kernel(float
 
       K2D_T(kT_Euler);
       // ---- positional corrections (A.3.7, A.4.1); the pair's accumulated impulses go to HBM ----
-      auto correct = [&](float nx, float ny, float corr, int ab, float4 lam) {
+      auto correct = [&](float nx, float ny, float corr, int ab, float4 lam, bool to_hbm) {
         const int a = ab & 0xff, b = (ab >> 8) & 0xff;
-        // the pair's accumulated impulses wait in the HBM record for the next substep (A.7)
-        if (env_ok) *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(a, b)) = lam;
+        // the pair's accumulated impulses wait for the next substep (A.7): the first pair of a lane in the
+        // lane's registers (see kept_lam), every other pair in the HBM record
+        if (to_hbm && env_ok) *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(a, b)) = lam;
         const float ima = E[L.inv_mass + a], imb = E[L.inv_mass + b];
         // (the positions of shapes no impulse moves go to the dump slot: L.pos_x is word 0 of the image)
         const int da = ((static_mask >> a) & 1u) ? K::X_DUMP : a, db = ((static_mask >> b) & 1u) ? K::X_DUMP : b;
@@ -1407,15 +1422,15 @@ __global__ void __launch_bounds__(64, K::EPW == 4 ? 2 : 1) k2d_step_kernel(float
       };
       for_each_level([&](typename S::Own& o) {
                        correct(o.rc.nx, o.rc.ny, o.rc.corr, o.rc.ab,
-                               make_float4(o.rc.lam_n[0], o.rc.lam_t[0], o.rc.lam_n[1], o.rc.lam_t[1]));
+                               make_float4(o.rc.lam_n[0], o.rc.lam_t[0], o.rc.lam_n[1], o.rc.lam_t[1]), &o == &ob);
                      },
                      [&](int q) {
                        if (q < K::POOL) {
                          LdsCF rp = to_lds(pool + q * kRecW);
-                         correct(rp[0], rp[1], rp[3], f2i(rp[4]), make_float4(rp[13], rp[14], rp[23], rp[24]));
+                         correct(rp[0], rp[1], rp[3], f2i(rp[4]), make_float4(rp[13], rp[14], rp[23], rp[24]), true);
                        } else {
                          const float* rp = spill + (q - K::POOL) * kRecW;
-                         correct(rp[0], rp[1], rp[3], f2i(rp[4]), make_float4(rp[13], rp[14], rp[23], rp[24]));
+                         correct(rp[0], rp[1], rp[3], f2i(rp[4]), make_float4(rp[13], rp[14], rp[23], rp[24]), true);
                        }
                      });
       kept_id = oa.id;
@@ -1459,6 +1474,7 @@ __global__ void __launch_bounds__(64, K::EPW == 4 ? 2 : 1) k2d_step_kernel(float
       }
     }
   }
+  flush_kept();
   // the joint accumulators return to the LDS image (from where a new pass, or the write-back, takes them)
   if (k < J) {
     E[L.acc_x + k] = j_accx;
