@@ -26,7 +26,8 @@ def _records(cfg, n, steps, noalloc):
 
 
 def test_noalloc_step_equals_step_twice_second_smaller():
-    for cfg, n, steps in ((2, 259, 24), (2, 67, 16)):      # launches long enough to use the ordering scratch
+    # (launches long enough to use the ordering scratch; the first batch is larger than one round of wavefronts)
+    for cfg, n, steps in ((0, 8451, 24), (0, 8259, 16)):
         want = _records(cfg, n, steps, noalloc=False)
         got = _records(cfg, n, steps, noalloc=True)
         assert want.shape == got.shape
@@ -35,6 +36,7 @@ def test_noalloc_step_equals_step_twice_second_smaller():
 
 
 def test_noalloc_step_other_capacity_class_after_it():
-    want = _records(1, 131, 16, noalloc=False)
-    got = _records(1, 131, 16, noalloc=True)
-    assert np.array_equal(want, got)
+    for cfg, n in ((1, 8323), (2, 131)):
+        want = _records(cfg, n, 16, noalloc=False)
+        got = _records(cfg, n, 16, noalloc=True)
+        assert np.array_equal(want, got)
