@@ -6,12 +6,16 @@
 // constraints (A.3.5-A.3.7), the Euler step, and the positional corrections (A.3.7, A.4.1).
 //
 // How it is mapped onto CDNA4:
-//   * One environment is owned by a group of G = 16 consecutive lanes, so a 64-wide wavefront steps four
-//     environments; a workgroup is exactly one wavefront, which makes every synchronisation point a
-//     wavefront-scope fence and lets the hardware place wavefronts on CUs freely.
+//   * One environment is owned by a group of G consecutive lanes: G = 16, so that a 64-wide wavefront
+//     steps four environments, or G = 8 and eight environments (chosen per launch: faster for the small
+//     capacity class in large batches).  A workgroup is exactly one wavefront, which makes every
+//     synchronisation point a wavefront-scope fence and lets the hardware place wavefronts on CUs freely.
 //   * The whole scene of an environment lives in LDS for the entire launch (all steps, substeps and
-//     solver sweeps); HBM is touched when the launch begins (one coalesced read of the record), once per
-//     step for the actions, and when it ends.  Lanes of a group exchange body velocities through LDS.
+//     solver sweeps).  HBM is touched when the launch begins (one coalesced read of the record), once per
+//     step for the actions, when it ends -- and in between only for the accumulated impulses (A.7) of
+//     pairs that change lanes because the set of colliding pairs changed, for the pair records of piles
+//     deeper than registers and LDS hold, and for the new scenes of restarted episodes.  Lanes of a group
+//     exchange body velocities through LDS.
 //   * Collision constraints are ordered by a round-robin tournament over the shapes: the pairs of one
 //     round touch disjoint shapes.  Of that order only what matters is kept: an active pair runs one
 //     dependency level after the last earlier active pair that shares a movable shape with it, all pairs
@@ -20,12 +24,15 @@
 //     batch-of-16 compromise).
 //   * Active manifolds of a substep become records that live in registers: lane k of the environment
 //     keeps active pairs k and G + k for the whole substep (warm start, all sweeps, corrections), so a
-//     visit costs one LDS round trip for the two bodies' velocities and nothing else.  Pairs beyond 2G
-//     stay in a small LDS pool, the rare excess beyond that spills to the environment's HBM record.
+//     visit costs one LDS round trip for the two bodies' velocities and nothing else; the accumulated
+//     impulses of pair k stay in the lane's registers from substep to substep while the set of colliding
+//     pairs is unchanged.  Pairs beyond 2G stay in a small LDS pool, the rare excess beyond that spills
+//     to the environment's HBM record.
 //   * Joints are solved in index order per shape (A.8: sequential); joints that share no shape are
 //     independent, so they are grouped into dependency levels once per episode and lane j solves joint j.
-//   * A launch of many steps first sorts the environments by expected work, so that the four of a
-//     wavefront are alike.
+//   * A launch of many steps first sorts the environments by expected work, so that the environments
+//     of a wavefront are alike: what a wavefront skips when none of its environments changed its set of
+//     colliding pairs (candidate list, dependency levels) it then skips more often.
 //
 // Nothing here is a dense contraction: no MFMA.  Arithmetic is fp32; the kernel is compiled without
 // automatic contraction of a*b+c; the fused multiply-adds are the ones written out (dot and cross
