@@ -62,7 +62,8 @@ struct Params {
   double joint_alpha = 6.0;            // joint point-constraint velocity correction, 1/s (A.4.1)
   double joint_beta = 0.2;             // joint positional correction                     (A.4.1)
   double tie_eps = 1e-3;               // reference face goes to b only if sep_b > sep_a + tie_eps
-  int order_mode = 0;                  // 0: canonical sequential; 1: each round from a snapshot (test)
+  int order_mode = 0;                  // 0: canonical sequential; 1: each colour class from a snapshot (test);
+                                       // 2: plain tournament order, no colours (comparison)
   int batch_size = 0;                  // 0: sequential sweep; B >= 1: batched impulse resolution (A.8)
 };
 constexpr int kNumParams = 17;
@@ -208,12 +209,14 @@ struct Env {
   std::vector<Joint<R>> joints;
   std::vector<Thruster<R>> thrusters;
   std::vector<Manifold<R>> manifolds;  // lexicographic pair order
+  std::vector<int> pair_colour;        // lexicographic pair order: colour of the pair at the last substep, -1 = not colliding
   std::vector<ContactAcc<R>> acc;      // lexicographic pair order
   double min_margin = std::numeric_limits<double>::infinity();
   // work counters, summed over substeps (they feed the benchmark's count of arithmetic, nothing else)
   int n_active_slots_sum = 0;          // active manifold points
   int n_active_pairs_sum = 0;          // pairs with at least one active point
   int n_pp_overlap_sum = 0;            // polygon pairs that went past the separating-axis test
+  int n_colours_sum = 0;               // colours (independent sets) of the colliding pairs, summed over substeps
   int n_substeps_done = 0;
 };
 
@@ -712,10 +715,50 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
     }
   }
 
-  // -- Warm starting (Alg. 1; A.7): collisions in canonical order, then joints in index order ------
+  // -- Visiting order of the colliding pairs (A.8).  The paper solves constraints one after the other
+  //    where it can afford to and says that the order of the active manifolds is the engine's to choose
+  //    (it spreads them over its batches).  Here: walk the colliding pairs in tournament order and give
+  //    each the smallest colour that no earlier colliding pair sharing a movable shape with it has
+  //    taken; visit colour 0 first, then colour 1, ..., tournament order inside a colour.  Pairs of one
+  //    colour share no shape that an impulse can move, so a colour is a set of independent constraints
+  //    and the sweep stays a sequential (Gauss-Seidel) one.  Shapes that no impulse moves (inactive, or
+  //    neither inverse mass nor inverse inertia) tie nothing together.
+  std::vector<int> visit;            // indices into cps, in visiting order
+  std::vector<int> colour_end;       // visit[colour_end[c-1] .. colour_end[c]) is colour c
+  {
+    auto movable = [&](int i) {
+      const Body<R>& s = E.bodies[i];
+      return s.active && (s.inv_mass != R(0) || s.inv_inertia != R(0));
+    };
+    std::vector<unsigned> taken(N, 0u);   // colours already used at each movable shape
+    std::vector<int> colour(cps.size(), -1);
+    int n_colours = 0;
+    for (size_t q = 0; q < cps.size(); ++q) {
+      E.pair_colour[pair_index(cps[q].a, cps[q].b, N)] = -1;
+      if (!cps[q].any) continue;
+      int c = 0;
+      if (P.order_mode != 2) {
+        unsigned busy = (movable(cps[q].a) ? taken[cps[q].a] : 0u) | (movable(cps[q].b) ? taken[cps[q].b] : 0u);
+        while ((busy >> c) & 1u) ++c;
+        if (movable(cps[q].a)) taken[cps[q].a] |= 1u << c;
+        if (movable(cps[q].b)) taken[cps[q].b] |= 1u << c;
+      }
+      colour[q] = c;
+      E.pair_colour[pair_index(cps[q].a, cps[q].b, N)] = c;
+      n_colours = std::max(n_colours, c + 1);
+    }
+    for (int c = 0; c < n_colours; ++c) {
+      for (size_t q = 0; q < cps.size(); ++q)
+        if (colour[q] == c) visit.push_back((int)q);
+      colour_end.push_back((int)visit.size());
+    }
+    E.n_colours_sum += n_colours;
+  }
+
+  // -- Warm starting (Alg. 1; A.7): collisions in visiting order, then joints in index order -------
   if (P.warm_start) {
-    for (ContactPair<R>& cp : cps) {
-      if (!cp.any) continue;
+    for (int q : visit) {
+      const ContactPair<R>& cp = cps[q];
       const ContactAcc<R>& acc = E.acc[pair_index(cp.a, cp.b, N)];
       for (int k = 0; k < 2; ++k) {
         if (!cp.row[k].active) continue;
@@ -744,26 +787,24 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
       if (jrs[q].live) solve_joint(E, E.joints[q], jrs[q]);
     if (P.batch_size > 0) {
       solve_contacts_batched(E, cps, N, P.batch_size);
-    } else if (P.order_mode == 0) {
-      for (ContactPair<R>& cp : cps)
-        if (cp.any) solve_contact_pair(E, cp, E.acc[pair_index(cp.a, cp.b, N)]);
+    } else if (P.order_mode != 1) {
+      for (int q : visit) solve_contact_pair(E, cps[q], E.acc[pair_index(cps[q].a, cps[q].b, N)]);
     } else {
-      // test mode: every pair of a round starts from the same snapshot of the bodies and only its
-      // own two bodies are copied back -- equal to the sequential sweep iff rounds are body-disjoint
-      size_t q = 0;
-      while (q < cps.size()) {
-        size_t q1 = q;
-        while (q1 < cps.size() && S.round[q1] == S.round[q]) ++q1;
+      // test mode: every pair of a colour starts from the same snapshot of the bodies and only what it
+      // did to its own two bodies is kept (for a shape that no impulse moves that is nothing) -- equal
+      // to the sequential sweep iff the pairs of a colour share no movable shape
+      int z0 = 0;
+      for (int z1 : colour_end) {
         std::vector<Body<R>> snap = E.bodies, out = E.bodies;
-        for (size_t z = q; z < q1; ++z) {
-          if (!cps[z].any) continue;
+        for (int z = z0; z < z1; ++z) {
+          ContactPair<R>& cp = cps[visit[z]];
           E.bodies = snap;
-          solve_contact_pair(E, cps[z], E.acc[pair_index(cps[z].a, cps[z].b, N)]);
-          out[cps[z].a] = E.bodies[cps[z].a];
-          out[cps[z].b] = E.bodies[cps[z].b];
+          solve_contact_pair(E, cp, E.acc[pair_index(cp.a, cp.b, N)]);
+          out[cp.a] = E.bodies[cp.a];
+          out[cp.b] = E.bodies[cp.b];
         }
         E.bodies = out;
-        q = q1;
+        z0 = z1;
       }
     }
   }
@@ -775,11 +816,11 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
     b.theta = b.theta + h * b.omega;
   }
 
-  // -- Positional corrections (A.3.7, A.4.1): colliding pairs in canonical order are moved apart by
+  // -- Positional corrections (A.3.7, A.4.1): colliding pairs in visiting order are moved apart by
   //    beta * (deepest penetration of the pair at the start of the substep, less the slop), shared
   //    in proportion to inverse mass; then joints in index order pull their anchors together.
-  for (const ContactPair<R>& cp : cps) {
-    if (!cp.any) continue;
+  for (int q : visit) {
+    const ContactPair<R>& cp = cps[q];
     const Manifold<R>& m = E.manifolds[pair_index(cp.a, cp.b, N)];
     R pen = R(0);
     for (int k = 0; k < 2; ++k) if (m.active[k]) pen = std::max(pen, m.pen[k]);
@@ -831,6 +872,7 @@ struct Batch : BatchBase {
       e.joints.resize(J);
       e.thrusters.resize(T);
       e.manifolds.resize(NP);
+      e.pair_colour.assign(NP, -1);
       e.acc.resize(NP);
     }
   }
@@ -892,11 +934,13 @@ struct Batch : BatchBase {
     FIELD("manifold_pen", NP * 2, e.manifolds[i / 2].pen[i % 2], RR)
     FIELD("manifold_normal", NP * 2, (i % 2 ? e.manifolds[i / 2].normal.y : e.manifolds[i / 2].normal.x), RR)
     FIELD("manifold_pos", NP * 4, (i % 2 ? e.manifolds[i / 4].pos[(i / 2) % 2].y : e.manifolds[i / 4].pos[(i / 2) % 2].x), RR)
+    FIELD("pair_colour", NP, e.pair_colour[i], II)
     FIELD("pair_margin", NP, e.manifolds[i].margin, double)
     FIELD("min_margin", 1, e.min_margin, double)
     FIELD("active_slots_sum", 1, e.n_active_slots_sum, II)
     FIELD("active_pairs_sum", 1, e.n_active_pairs_sum, II)
     FIELD("pp_overlap_sum", 1, e.n_pp_overlap_sum, II)
+    FIELD("colours_sum", 1, e.n_colours_sum, II)
     FIELD("substeps_done", 1, e.n_substeps_done, II)
 #undef FIELD
 #undef RR

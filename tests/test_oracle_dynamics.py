@@ -450,9 +450,118 @@ def test_schedule_is_a_round_robin(N):
     assert (np.diff(r) >= 0).all()
 
 
-def test_round_at_once_equals_sequential_sweep():
-    """Solving every pair of a round from the same snapshot gives bit-identical results to the
-    sequential sweep: the rounds of the canonical order are conflict-free."""
+def _movable(st_or_sc, e, i):
+    return st_or_sc["active"][e, i] > 0 and (st_or_sc["inv_mass"][e, i] != 0 or st_or_sc["inv_inertia"][e, i] != 0)
+
+
+def _visiting_order(N, colliding, movable):
+    """Written out here a second time, from the rule: walk the colliding pairs in tournament order, give each the
+    lowest level no earlier colliding pair sharing a movable shape with it has taken.  Returns {(a, b): level} and
+    {(a, b): dependency level} (one past the last earlier pair sharing a movable shape), for comparison."""
+    a, b, r = ko.schedule(N)
+    taken, last, level, dep = {}, {}, {}, {}
+    for x, y, rr in zip(a.tolist(), b.tolist(), r.tolist()):
+        if (x, y) not in colliding:
+            continue
+        ends = [s for s in (x, y) if movable(s)]
+        busy = set().union(*[taken.get(s, set()) for s in ends]) if ends else set()
+        lv = next(c for c in range(64) if c not in busy)
+        d = max([last.get(s, 0) for s in ends], default=0)
+        for s in ends:
+            taken.setdefault(s, set()).add(lv)
+            last[s] = d + 1
+        level[(x, y)], dep[(x, y)] = lv, d
+        assert lv <= d <= rr
+    return level, dep
+
+
+@pytest.mark.parametrize("workload", ["config 3", "dense pile", "towers"])
+def test_visiting_order_is_the_lowest_free_level_walk_of_the_tournament_order(workload):
+    """The order of the sweep over the colliding pairs (A.8 leaves it to the engine): the oracle's levels equal
+    the ones worked out here from the colliding set alone; pairs of one level share no movable shape; a level is
+    never later than the place the pair would have one past its last conflicting predecessor, and on piles it
+    is often earlier."""
+    n = 16
+    if workload == "config 3":
+        caps, p, sc = scenegen.make_scene(3, n_envs=n)
+        act = scenegen.make_actions(3, 60, n)
+    elif workload == "dense pile":
+        caps, p, sc = scenegen.make_dense_scene(n_envs=n)
+        act = scenegen.make_actions(3, 120, n)
+    else:
+        caps, p, sc = scenegen.make_stack_scene(n_envs=n)
+        act = np.zeros((20, n, caps[2] + caps[3]))
+    N = caps[0] + caps[1]
+    o = Oracle(caps, n, p, "f32")
+    o.load_scene(sc)
+    o.step(act)
+    colour = o.get("pair_colour").reshape(n, -1)
+    active = o.get("pair_active").reshape(n, -1, 2).any(-1)
+    earlier = 0
+    for e in range(n):
+        colliding = {(i, j) for i in range(N) for j in range(i + 1, N) if active[e, pair_index(i, j, N)]}
+        level, dep = _visiting_order(N, colliding, lambda i: _movable(sc, e, i))
+        for i in range(N):
+            for j in range(i + 1, N):
+                assert colour[e, pair_index(i, j, N)] == level.get((i, j), -1), (e, i, j)
+        for lv in set(level.values()):
+            ends = [s for pr, l in level.items() if l == lv for s in pr if _movable(sc, e, s)]
+            assert len(ends) == len(set(ends))
+        earlier += sum(level[pr] < dep[pr] for pr in level)
+    assert active.sum() > 3 * n
+    if workload != "config 3":
+        assert earlier > 0
+
+
+def test_sweep_visits_the_levels_in_order_closed_form():
+    """Four equal frictionless balls in a row, no gravity, no restitution, one sweep: a colliding pair that
+    approaches ends at the mean of its two velocities.  The outcome depends on the order of the three contacts;
+    the oracle's equals the one worked out here for the level-by-level order (the outer contacts, then the
+    middle one) and, with the plain tournament order switched on, the one for that order."""
+    caps = (1, 4, 1, 1)
+    N, r, pen = 5, 0.5, 1e-4
+    a, b, _ = ko.schedule(N)
+    place = None
+    for perm in ((1, 2, 3, 4), (1, 3, 2, 4), (2, 1, 4, 3), (1, 2, 4, 3), (3, 1, 2, 4), (1, 4, 2, 3)):
+        contacts = {tuple(sorted((perm[q], perm[q + 1]))) for q in range(3)}
+        walk = [(x, y) for x, y in zip(a.tolist(), b.tolist()) if (x, y) in contacts]
+        if set(walk[1]) & set(perm[1:3]) == set(perm[1:3]):    # the middle contact is walked second
+            place = perm
+            break
+    assert place is not None
+    v0 = {place[0]: 1.0, place[1]: 0.0, place[2]: 0.0, place[3]: -1.0}
+
+    def expected(order):
+        v = dict(v0)
+        x_of = {s: q for q, s in enumerate(place)}
+        for x, y in order:
+            lo, hi = (x, y) if x_of[x] < x_of[y] else (y, x)
+            if v[lo] > v[hi]:
+                v[lo] = v[hi] = 0.5 * (v[lo] + v[hi])
+        return v
+
+    level, _ = _visiting_order(N, contacts, lambda i: True)
+    by_level = sorted(walk, key=lambda pr: (level[pr], walk.index(pr)))
+    assert by_level != walk and expected(by_level) != expected(walk)
+    for mode, order in ((0, by_level), (2, walk)):
+        sb = SceneBuilder(caps)
+        ids = {}
+        for k in range(4):
+            ids[k + 1] = sb.circle(r, (0.0, 0.0), friction=0.0)
+        for q, s in enumerate(place):
+            sb.sc["pos"][0, s] = (q * (2 * r - pen), 3.0)
+            sb.sc["vel"][0, s] = (v0[s], 0.0)
+        o, _ = run(sb, params(n_iters=1, gravity_y=0.0, warm_start=0, order_mode=mode), caps=caps)
+        o.step(zeros_actions(1, 1, caps))
+        vel = o.state()["vel"].reshape(-1, 2)
+        want = expected(order)
+        for s in place:
+            assert vel[s, 0] == pytest.approx(want[s], abs=1e-12) and vel[s, 1] == 0.0
+
+
+def test_level_at_once_equals_sequential_sweep():
+    """Solving every pair of a level from the same snapshot gives bit-identical results to visiting them one
+    after the other: the levels of the visiting order are conflict-free."""
     caps, p, sc = scenegen.make_scene(3, n_envs=24)
     act = scenegen.make_actions(3, 40, 24)
     out = []
@@ -666,8 +775,8 @@ def test_batch_size_one_is_the_sequential_sweep():
     caps, p, sc = scenegen.make_scene(3, n_envs=16)
     act = scenegen.make_actions(3, 30, 16)
     out = []
-    for B in (0, 1, 16):
-        o = Oracle(caps, 16, dict(p, batch_size=B), "f32")
+    for B in (0, 1, 16):       # (the batches walk the plain tournament order: compared with the sweep in that order)
+        o = Oracle(caps, 16, dict(p, batch_size=B, order_mode=2), "f32")
         o.load_scene(sc)
         o.step(act)
         out.append(o.state())
