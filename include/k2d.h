@@ -53,11 +53,15 @@ typedef struct {
   float joint_alpha;           /* A.4.1 velocity correction of the joint point constraint, 1/s         */
   float joint_beta;            /* A.4.1 positional correction of the joint point constraint            */
   float tie_eps;               /* A.3.4: b's face is the reference face only if it wins by tie_eps     */
-  int32_t batch_size;          /* A.8: 0 = collision constraints one after the other in canonical order */
-                               /* (run level by level, same bits); B in 1..K2D_MAX_BATCH_SIZE = the     */
-                               /* manifold points, two per pair in canonical order, dealt in turn over  */
-                               /* ceil(points / B) batches; a batch is solved from the velocities it    */
-                               /* starts with and its impulses applied in point order (16 in the paper) */
+  int32_t batch_size;          /* A.8: 0 = collision constraints one after the other, level after level */
+                               /* (the colliding pairs are walked in the order of a round-robin         */
+                               /* tournament over the shapes; each takes the lowest level that no       */
+                               /* earlier colliding pair sharing a movable shape with it has taken; the */
+                               /* pairs of a level are independent and are solved at once, same bits);  */
+                               /* B in 1..K2D_MAX_BATCH_SIZE = the manifold points, two per pair in     */
+                               /* tournament order, dealt in turn over ceil(points / B) batches; a      */
+                               /* batch is solved from the velocities it starts with and its impulses   */
+                               /* applied in point order (16 in the paper)                              */
 } k2d_params;
 #define K2D_MAX_BATCH_SIZE 32
 
@@ -115,8 +119,8 @@ int k2d_alloc_batch(const k2d_caps* caps, const k2d_params* params, int n_envs, 
 /* How the step kernel maps environments onto the 64 lanes of a wavefront: `lanes` = 16 (four environments
  * per wavefront), 8 (eight per wavefront: half the instructions per environment, twice the on-chip memory
  * per wavefront), or 0 = chosen per launch (the default: 8 lanes for Small environments in batches of more
- * than 8192, where that is faster, 16 otherwise).  The mapping changes no result (the pairs of a round of
- * the canonical order touch disjoint shapes, A.8, whichever lanes hold them).  With 8 lanes the batched
+ * than 8192, where that is faster, 16 otherwise).  The mapping changes no result (the pairs of a level of
+ * the sweep touch disjoint movable shapes, A.8, whichever lanes hold them).  With 8 lanes the batched
  * schedule takes batch sizes up to 16 (the paper's).  K2D_E_ARG otherwise. */
 int k2d_set_lanes_per_env(k2d_batch* batch, int lanes);
 

@@ -18,7 +18,8 @@
 // Pins (tests/test_oracle_*.py): closed-form free fall under semi-implicit Euler, head-on circle
 // collisions with restitution, box resting on a floor, energy non-increase without actuation,
 // pendulum drift and period, motor tanh law, thruster closed form, warm-start bookkeeping, brute-force
-// point-sampled overlap for the narrowphase, hand-evaluated manifolds, round-parallel == sequential,
+// point-sampled overlap for the narrowphase, hand-evaluated manifolds, the visiting order of the sweep
+// (levels recomputed from the colliding set, four balls in a row in closed form, level-at-once == sequential),
 // joint limits (closed form of one visit, symmetry, restoring motion untouched), towers of boxes standing,
 // batched impulse resolution (closed form of two constraints on one body solved in one batch, batch size 1
 // == sequential, momentum, the stability trade-off of A.8 on the towers).
@@ -62,8 +63,8 @@ struct Params {
   double joint_alpha = 6.0;            // joint point-constraint velocity correction, 1/s (A.4.1)
   double joint_beta = 0.2;             // joint positional correction                     (A.4.1)
   double tie_eps = 1e-3;               // reference face goes to b only if sep_b > sep_a + tie_eps
-  int order_mode = 0;                  // 0: canonical sequential; 1: each colour class from a snapshot (test);
-                                       // 2: plain tournament order, no colours (comparison)
+  int order_mode = 0;                  // 0: level after level (the visiting order below); 1: each level from a snapshot (test);
+                                       // 2: plain tournament order, no levels (comparison)
   int batch_size = 0;                  // 0: sequential sweep; B >= 1: batched impulse resolution (A.8)
 };
 constexpr int kNumParams = 17;
@@ -222,13 +223,13 @@ struct Env {
 
 inline int pair_index(int i, int j, int N) { return i * (2 * N - i - 1) / 2 + (j - i - 1); }
 
-// Canonical order in which collision constraints are visited: a round-robin tournament over the
-// shape indices.  All pairs of one round touch disjoint shapes, so the sequential sweep below gives
-// the same numbers as solving a whole round at once.  This is the batch-size-1 end of the
-// speed/stability family of A.8 (sequential is the stable ideal), visited in a conflict-free order.
+// The order in which shape pairs are walked: a round-robin tournament over the shape indices (all
+// pairs of one round touch disjoint shapes).  The batched schedule of A.8 deals the manifold points
+// over its batches in this order; the sequential sweep derives its visiting order from it (see
+// "Visiting order of the colliding pairs" in substep()).
 struct Schedule {
   int n_rounds = 0, per_round = 0;
-  std::vector<int> a, b, round;   // in visiting order
+  std::vector<int> a, b, round;   // in tournament order
 };
 Schedule make_schedule(int N) {
   Schedule s;
@@ -486,7 +487,7 @@ void solve_contact_pair(Env<R>& E, ContactPair<R>& cp, ContactAcc<R>& acc) {
     if (cp.row[k].active) solve_contact_point(E.bodies[cp.a], E.bodies[cp.b], cp, k, acc, j, jf);
 }
 
-// Batched impulse resolution (A.8): the manifold points -- two per shape pair, pairs in canonical order --
+// Batched impulse resolution (A.8): the manifold points -- two per shape pair, pairs in tournament order --
 // are dealt in turn over n_b = ceil(points / B) batches, so that neighbouring points (which tend to be
 // active together) land in different batches and a batch holds at most B points.  The batches are
 // solved one after the other; the active points of one batch are all solved from the velocities the
@@ -716,13 +717,14 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
   }
 
   // -- Visiting order of the colliding pairs (A.8).  The paper solves constraints one after the other
-  //    where it can afford to and says that the order of the active manifolds is the engine's to choose
-  //    (it spreads them over its batches).  Here: walk the colliding pairs in tournament order and give
-  //    each the smallest colour that no earlier colliding pair sharing a movable shape with it has
-  //    taken; visit colour 0 first, then colour 1, ..., tournament order inside a colour.  Pairs of one
-  //    colour share no shape that an impulse can move, so a colour is a set of independent constraints
-  //    and the sweep stays a sequential (Gauss-Seidel) one.  Shapes that no impulse moves (inactive, or
-  //    neither inverse mass nor inverse inertia) tie nothing together.
+  //    where it can afford to, and leaves the order of the active manifolds to the engine (its own
+  //    spreads them over its batches).  Here: walk the colliding pairs in tournament order and give
+  //    each the lowest level that no earlier colliding pair sharing a movable shape with it has taken;
+  //    visit level 0 first, then level 1, ..., tournament order inside a level.  Pairs of one level
+  //    share no shape that an impulse can move, so a level is a set of independent constraints and the
+  //    sweep stays a sequential (Gauss-Seidel) one, as short as the busiest shape's contacts allow.
+  //    Shapes that no impulse moves (inactive, or neither inverse mass nor inverse inertia) tie nothing
+  //    together.
   std::vector<int> visit;            // indices into cps, in visiting order
   std::vector<int> colour_end;       // visit[colour_end[c-1] .. colour_end[c]) is colour c
   {
@@ -781,7 +783,7 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
     }
   }
 
-  // -- Solver sweeps (Alg. 1): joints sequentially (A.8), then collisions in canonical order -------
+  // -- Solver sweeps (Alg. 1): joints sequentially (A.8), then collisions in visiting order --------
   for (int it = 0; it < P.n_iters; ++it) {
     for (int q = 0; q < nJ; ++q)
       if (jrs[q].live) solve_joint(E, E.joints[q], jrs[q]);

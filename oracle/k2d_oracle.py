@@ -2,7 +2,7 @@
 
 Only tests, the smoke check and the CPU-baseline leg of the benchmark import this module.  It builds
 `libk2d_oracle.so` from `k2d_oracle.cpp` with g++ on demand and exposes the batch object, the stand-alone
-manifold routines and the canonical pair order.  It imports nothing from the GPU package.
+manifold routines and the tournament order of the shape pairs.  It imports nothing from the GPU package.
 """
 import ctypes
 import os

@@ -157,7 +157,7 @@ struct Cfg {
                                                            // grown by kCullMargin on every side
   static constexpr int X_WV = X_BOX + 4 * N;               // world vertices, float2 [4][P]
   static constexpr int X_WN = X_WV + 8 * P;                // outward unit edge normals, float2 [4][P]
-  static constexpr int NID = R * GP;                       // pair ids: id = r * GP + k (canonical order)
+  static constexpr int NID = R * GP;                       // pair ids: id = r * GP + k (tournament order)
   static constexpr int X_TABLE = align_up(X_WN + 8 * P, 4);        // bytes [NID]: number of the active pair with this id (set for the pairs not held in registers)
   static constexpr int TABLE_W = align_up((NID + 3) / 4, 4);       // read back four words at a time
   static constexpr int X_LIST = X_TABLE + TABLE_W;         // bytes [NID]: candidate ids, one shape-type mix after the other
@@ -578,7 +578,7 @@ struct Step {
     if (q) { rc.lam_n[1] = ln; rc.lam_t[1] = lt; }
     else { rc.lam_n[0] = ln; rc.lam_t[0] = lt; }
   }
-  // Where the two points of pair `id` (canonical order) fall in the batched schedule: the points, two per
+  // Where the two points of pair `id` (tournament order) fall in the batched schedule: the points, two per
   // pair, are dealt in turn over n_b batches.  Returns batch | place<<8 of point 0, the same <<16 of point 1.
   static __device__ __forceinline__ int batch_places(int id, int n_b) {
     constexpr int odd = N & 1;   // the phantom's pair (slot 0 of every round) is not a pair
@@ -626,7 +626,7 @@ struct Step {
     float ima, iia, imb, iib;
     int pa, pb;   // shape indices
     int sa, sb;   // where the velocities go back: the shape itself, or the dump slot if no impulse moves it
-    int id;       // pair id in canonical order, -1 = nothing held
+    int id;       // pair id in tournament order, -1 = nothing held
     int lv;       // dependency level of this substep
   };
   // Substep constants of an active pair from its manifold (A.3.5-A.3.7) and the accumulated impulses it
@@ -1237,7 +1237,7 @@ __global__ void __launch_bounds__(64, K::EPW == 4 ? 2 : 1) k2d_step_kernel(float
 #ifdef K2D_PHASE_TIMERS
       t_pair_levels += wave_clevels; t_joint_levels += wave_levels;
 #endif
-      // ---- warm starting (Alg. 1, A.7): collisions in canonical order, then joints ----
+      // ---- warm starting (Alg. 1, A.7): collisions level after level, then joints ----
       if (prm.warm_start) {
         for_each_level([&](typename S::Own& o) { S::template visit_own<true>(E, o); },
                        [&](int q) {

@@ -156,9 +156,10 @@ I_JOINT_WARM = 12
 def sequential_chain_instructions(caps, scene, params, pair_points, schedule):
     """Length, in instructions, of the chain of constraint visits that the sweep order forces to run one
     after the other in one substep of every environment: constraints that share a movable shape keep their
-    order (joints in index order, collisions in canonical order, Algorithm 1 and A.8), the others may run
-    side by side.  pair_points [E, n_pairs] = active manifold points per pair (lexicographic pair order) of a
-    sampled substep; schedule = (a[], b[]) canonical visiting order.  A visit of a pair costs its points one
+    order (joints in index order; collisions level after level, a pair taking the lowest level that no
+    earlier colliding pair of the tournament order sharing a movable shape with it has; Algorithm 1 and A.8),
+    the others may run side by side.  pair_points [E, n_pairs] = active manifold points per pair
+    (lexicographic pair order) of a sampled substep; schedule = (a[], b[]) tournament order.  A visit of a pair costs its points one
     after the other; a level costs its longest visit.  Returns an array [E]: instructions per substep for
     warm starting plus `n_iters` sweeps -- at best one instruction every four clocks on one wavefront."""
     P, C, J, T = caps
@@ -184,18 +185,21 @@ def sequential_chain_instructions(caps, scene, params, pair_points, schedule):
                 nxt[a] = lv + 1
             if movable[e, b]:
                 nxt[b] = lv + 1
-        nxt[:] = 0
+        taken = [0] * N                          # collisions: levels already taken at every shape
         pl_pts = {}
         for a, b, pi in zip(sa, sb, pidx):
             npt = int(pair_points[e, pi])
             if npt == 0:
                 continue
-            lv = max(nxt[a] if movable[e, a] else 0, nxt[b] if movable[e, b] else 0)
+            busy = (taken[a] if movable[e, a] else 0) | (taken[b] if movable[e, b] else 0)
+            lv = 0
+            while (busy >> lv) & 1:
+                lv += 1
             pl_pts[lv] = max(pl_pts.get(lv, 0), npt)
             if movable[e, a]:
-                nxt[a] = lv + 1
+                taken[a] |= 1 << lv
             if movable[e, b]:
-                nxt[b] = lv + 1
+                taken[b] |= 1 << lv
         sweep = sum(jl_cost.values()) + I_POINT_VISIT * sum(pl_pts.values())
         warm = (I_JOINT_WARM * len(jl_cost) + I_POINT_WARM * sum(pl_pts.values())) if params["warm_start"] else 0
         out[e] = params["n_iters"] * sweep + warm

@@ -1,7 +1,7 @@
 """Pins of the oracle's dynamics (paper Algorithm 1, A.2, A.3.5-A.3.7, A.4-A.7) against closed forms and
 invariants: free fall under semi-implicit Euler, head-on collisions with restitution, resting box,
-energy, friction, pendulum, fixed joint, motor law, thruster impulse, warm-start bookkeeping, canonical
-order."""
+energy, friction, pendulum, fixed joint, motor law, thruster impulse, warm-start bookkeeping, the order
+of the sweep."""
 import numpy as np
 import pytest
 
@@ -438,7 +438,7 @@ def test_warm_start_off_and_on_reach_the_same_rest_but_on_is_faster():
     assert res[1] < 1e-3 and res[1] <= res[0]
 
 
-# ------------------------------------------------------------------ canonical order (A.8)
+# ------------------------------------------------------------------ order of the sweep (A.8)
 @pytest.mark.parametrize("N", [7, 9, 16])
 def test_schedule_is_a_round_robin(N):
     a, b, r = ko.schedule(N)
