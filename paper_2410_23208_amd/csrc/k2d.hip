@@ -1962,6 +1962,7 @@ int scratch_of_current_device(int32_t** out) {
 #ifdef K2D_PHASE_TIMERS
 unsigned long long* g_phase_clocks = nullptr;   // caller-owned device buffer, kPhaseSlots words per wavefront
 long g_phase_waves = 0;
+bool g_phase_keep_order = false;                // launches take the environments as they are numbered
 #endif
 
 template <class K, bool RESET, bool BATCHED>
@@ -2045,6 +2046,9 @@ static int step_launch_as(k2d_batch* b, const float* actions_dev, int n_envs, in
   // wavefront are then alike, and what a wavefront skips when none of its environments changed (candidate
   // list, dependency levels) it skips more often (7 % of the launch time on the Large workload).
   int32_t* ord = n_steps >= kOrderMinSteps ? order_buf : nullptr;
+#ifdef K2D_PHASE_TIMERS
+  if (g_phase_keep_order) ord = nullptr;
+#endif
   // lane mapping: as set on the batch; else 16 lanes per environment, except for Small environments in
   // batches larger than that mapping keeps resident at once.  (Measured on MI355X: with 8 lanes the Small
   // class steps 16384 and more environments 1.5 to 1.7 times faster; the Medium and Large classes are
@@ -2088,6 +2092,12 @@ int k2d_debug_set_phase_buffer(void* clocks_dev, long n_waves) {
   g_phase_clocks = static_cast<unsigned long long*>(clocks_dev);
   g_phase_waves = clocks_dev ? n_waves : 0;
   return kPhaseSlots;
+}
+// Instrumented build only: launches keep the environments in the order of their numbers (no sorting by
+// expected work), so that a measurement can decide which environments share a wavefront.
+int k2d_debug_keep_order(int on) {
+  g_phase_keep_order = on != 0;
+  return K2D_OK;
 }
 #endif
 
