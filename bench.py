@@ -52,7 +52,7 @@ def main():
                     help="config = the workload --config names; dense = workload 3's heap in a narrow pen "
                          "(contact-heavy), towers = stacks of boxes (A.7); both 8192 environments x 256 steps")
     ap.add_argument("--cpu-envs", type=int, default=8192, help="environments of the CPU-oracle sample")
-    ap.add_argument("--batch-size", type=int, default=0, help="0 = the default schedule (dependency levels, the "
+    ap.add_argument("--batch-size", type=int, default=0, help="0 = the default schedule (levels of independent constraints: a "
                     "sequential sweep's bits); 1..32 = the batched impulse resolution of A.8 with that batch size")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain 256 MiB device copy, so "
                     "that a counter run has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -200,7 +200,7 @@ def main():
         "config": {"workload": "%s, %d envs x %d steps, %d substeps x %d solver sweeps, caps P/C/J/T=%s"
                    % (wl_name, n_envs, n_steps, params["n_substeps"], params["n_iters"], "/".join(map(str, caps))),
                    "env_steps_per_launch": env_steps, "seed": scenegen.SEED,
-                   "schedule": "dependency levels" if args.batch_size == 0 else "batches of %d (A.8)" % args.batch_size},
+                   "schedule": "sequential sweep, level after level" if args.batch_size == 0 else "batches of %d (A.8)" % args.batch_size},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / FP32_VALU_PEAK_TFLOPS, "traffic": traffic, "traffic_profiled_at": traffic_at,
                      "frac_nonpacked": achieved / FP32_VALU_PEAK_NONPACKED,

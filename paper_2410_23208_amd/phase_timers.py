@@ -21,7 +21,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
 
 PHASES = ["actions", "gravity + world polygons", "joint constants", "motors + thrusters", "cull + candidate list",
-          "manifolds", "take + pre-solve", "dependency levels", "warm start", "sweeps: joints", "sweeps: collisions",
+          "manifolds", "take + pre-solve", "levels of the pairs", "warm start", "sweeps: joints", "sweeps: collisions",
           "Euler step", "corrections: collisions", "corrections: joints", "restarts / tail"]
 
 
