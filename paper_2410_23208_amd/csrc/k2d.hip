@@ -1809,20 +1809,78 @@ __global__ void k2d_order_keys_kernel(const float* state, int32_t* keys, int n_e
   static_assert(14 * 68 + 16 * 4 + 3 < kOrderKeys, "key range");
   keys[env] = kOrderKeys - 1 - (min(pairs, 14) * 68 + min(movable, 16) * 4 + min(depth, 3));   // busiest first
 }
-__global__ void __launch_bounds__(1024) k2d_order_kernel(const int32_t* keys, int32_t* order, int n_envs, int n_slots) {
-  __shared__ int count[kOrderKeys], start[kOrderKeys];
+// The counting sort.  Slots are handed out in key order (slot s belongs to wavefront s / envs_per_wave), so the
+// environments of a wavefront have the same or neighbouring keys.  Inside a key the environments are free to
+// trade places, and that freedom is used for the L2: wavefront w of the step kernel runs on XCD w % 8
+// (workgroups go to the eight XCDs in turn) and every XCD has an L2 of its own, so the environments whose action
+// rows share a 128-byte line (`envs_per_line` neighbours; class c = (env / envs_per_line) % 8) look for a slot
+// on XCD c among the slots of their key: the line that one of them fetches is then in the L2 that the others
+// ask.  The environments of a key that find the slots of their class taken (the classes of a key are not equally
+// large) take what the other classes of the key leave free.
+constexpr int kOrderClasses = 8;
+__global__ void __launch_bounds__(1024) k2d_order_kernel(int32_t* keys, int32_t* order, int n_envs, int n_waves,
+                                                         int envs_per_wave, int envs_per_line) {
+  __shared__ int count[kOrderKeys * kOrderClasses];   // histogram over (key, class); then ranks
+  __shared__ int part[1024];
   const int t = threadIdx.x;
-  for (int q = t; q < kOrderKeys; q += blockDim.x) count[q] = 0;
+  auto class_of = [&](int env) { return (env / envs_per_line) % kOrderClasses; };
+  for (int q = t; q < kOrderKeys * kOrderClasses; q += blockDim.x) count[q] = 0;
   __syncthreads();
-  for (int env = t; env < n_envs; env += blockDim.x) atomicAdd(&count[keys[env]], 1);
+  for (int env = t; env < n_envs; env += blockDim.x) atomicAdd(&count[keys[env] * kOrderClasses + class_of(env)], 1);
   __syncthreads();
-  if (t == 0) {
-    int acc = 0;
-    for (int q = 0; q < kOrderKeys; ++q) { start[q] = acc; acc += count[q]; }
+  // exclusive prefix sum over the bins: thread t owns the bins of key t
+  static_assert(kOrderKeys == 1024, "one thread per key");
+  int mine = 0;
+  for (int c = 0; c < kOrderClasses; ++c) mine += count[t * kOrderClasses + c];
+  part[t] = mine;
+  __syncthreads();
+  for (int d = 1; d < 1024; d <<= 1) {
+    const int v = t >= d ? part[t - d] : 0;
+    __syncthreads();
+    part[t] += v;
+    __syncthreads();
   }
-  for (int sl = t; sl < n_slots; sl += blockDim.x) order[sl] = -1;
+  int acc = part[t] - mine;
+  for (int c = 0; c < kOrderClasses; ++c) { const int n = count[t * kOrderClasses + c]; count[t * kOrderClasses + c] = acc; acc += n; }
+  for (int sl = t; sl < n_waves * envs_per_wave; sl += blockDim.x) order[sl] = -1;
   __syncthreads();
-  for (int env = t; env < n_envs; env += blockDim.x) order[atomicAdd(&start[keys[env]], 1)] = env;
+  // every environment draws its rank (key-major, class-minor); the rank is kept beside the key
+  for (int env = t; env < n_envs; env += blockDim.x) {
+    const int key = keys[env];
+    const int r = atomicAdd(&count[key * kOrderClasses + class_of(env)], 1);
+    keys[env] = key | (r << 10);
+  }
+  __syncthreads();
+  // now count[x] is the first rank of bin x + 1: the bins' boundaries can be read off again
+  auto first_rank = [&](int x) { return x > 0 ? count[x - 1] : 0; };
+  const int wave_slots = envs_per_wave, period = kOrderClasses * envs_per_wave;
+  // slots below s that lie on XCD c, and the j-th slot of XCD c
+  auto slots_before = [&](int c, int s) {
+    const int full = s / period, rem = s % period;
+    return full * wave_slots + min(max(rem - c * wave_slots, 0), wave_slots);
+  };
+  auto slot_of = [&](int c, int j) { return ((j / wave_slots) * kOrderClasses + c) * wave_slots + j % wave_slots; };
+  for (int env = t; env < n_envs; env += blockDim.x) {
+    const int key = keys[env] & 1023, r = keys[env] >> 10, c = class_of(env);
+    const int r0 = first_rank(key * kOrderClasses), r1 = count[key * kOrderClasses + kOrderClasses - 1];   // the key's slots
+    const int i = r - first_rank(key * kOrderClasses + c);                                               // place within (key, class)
+    const int have = slots_before(c, r1) - slots_before(c, r0);
+    if (i < have) {
+      order[slot_of(c, slots_before(c, r0) + i)] = env;
+    } else {   // the o-th environment of the key without a slot on its XCD takes the o-th slot the key has left
+      int o = i - have;
+      for (int c2 = 0; c2 < c; ++c2) {
+        const int n2 = count[key * kOrderClasses + c2] - first_rank(key * kOrderClasses + c2);
+        o += max(0, n2 - (slots_before(c2, r1) - slots_before(c2, r0)));
+      }
+      for (int c2 = 0; c2 < kOrderClasses; ++c2) {
+        const int n2 = count[key * kOrderClasses + c2] - first_rank(key * kOrderClasses + c2);
+        const int fre = max(0, (slots_before(c2, r1) - slots_before(c2, r0)) - n2);
+        if (o < fre) { order[slot_of(c2, slots_before(c2, r0) + n2 + o)] = env; break; }
+        o -= fre;
+      }
+    }
+  }
 }
 
 // Reward and termination (Sec. 3.2): 16 lanes per environment, lane i looks at shape i.  A green shape in
@@ -1987,7 +2045,9 @@ int launch_step(float* state, const float* actions, int n_envs, int n_steps, con
     int32_t* keys = order + grid * K::EPW;
     K2D_LAUNCH(ok, k2d_order_keys_kernel, dim3((n_envs + 255) / 256), dim3(256), 0, st, state, keys, n_envs, rec_words,
                        layout, K::J);
-    K2D_LAUNCH(ok, k2d_order_kernel, dim3(1), dim3(1024), 0, st, keys, order, n_envs, grid * K::EPW);
+    // action rows that share a 128-byte line (rows of K::A floats; at least one environment per line)
+    const int envs_per_line = K::A > 0 && 32 / K::A > 0 ? 32 / K::A : 1;
+    K2D_LAUNCH(ok, k2d_order_kernel, dim3(1), dim3(1024), 0, st, keys, order, n_envs, grid, K::EPW, envs_per_line);
   }
 #ifdef K2D_PHASE_TIMERS
   K2D_LAUNCH(ok, (k2d_step_kernel<K, RESET, BATCHED>), dim3(grid), dim3(64), K::LDS_BYTES, st, state, actions, n_envs,
@@ -2015,6 +2075,8 @@ struct k2d_batch {
 
 // launches of fewer steps than this keep the identity ordering (the ordering pass would cost more than it could save)
 constexpr int kOrderMinSteps = 8;
+// the counting sort keeps an environment's rank in 21 bits beside its key
+constexpr int kOrderMaxEnvs = 1 << 21;
 static size_t records_bytes(int cls, int n_envs) {
   return ((size_t)n_envs * rec_words_of(cls) * sizeof(float) + 255) / 256 * 256;
 }
@@ -2045,7 +2107,7 @@ static int step_launch_as(k2d_batch* b, const float* actions_dev, int n_envs, in
   // A launch of many steps takes its environments in the order of their expected work: the four of a
   // wavefront are then alike, and what a wavefront skips when none of its environments changed (candidate
   // list, dependency levels) it skips more often (7 % of the launch time on the Large workload).
-  int32_t* ord = n_steps >= kOrderMinSteps ? order_buf : nullptr;
+  int32_t* ord = (n_steps >= kOrderMinSteps && n_envs < kOrderMaxEnvs) ? order_buf : nullptr;
 #ifdef K2D_PHASE_TIMERS
   if (g_phase_keep_order) ord = nullptr;
 #endif
