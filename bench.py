@@ -7,7 +7,7 @@ steps, 3 substeps x 10 solver sweeps), starting from the freshly reset synthetic
 actions) are resident in HBM before the timed region.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..4] [--workload config|dense|towers]
-                  [--cpu-envs N] [--no-cpu]
+                  [--batch-size B] [--sweep-order tournament|levels] [--cpu-envs N] [--no-cpu]
 """
 import argparse
 import json
@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--cpu-envs", type=int, default=8192, help="environments of the CPU-oracle sample")
     ap.add_argument("--batch-size", type=int, default=0, help="0 = the default schedule (levels of independent constraints: a "
                     "sequential sweep's bits); 1..32 = the batched impulse resolution of A.8 with that batch size")
+    ap.add_argument("--sweep-order", default="tournament", choices=["tournament", "levels"],
+                    help="visiting order of the colliding pairs in a sweep (k2d_params.sweep_order): the order of "
+                    "a round-robin tournament over the shapes (default), or level after level (lowest free level)")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain 256 MiB device copy, so "
                     "that a counter run has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg (flop model then uses "
@@ -89,7 +92,7 @@ def main():
             actions_h = np.zeros((n_steps, n_envs, caps[2] + caps[3]), dtype=np.float32)
         cfg = dict(name=args.workload)
         wl_name = {"dense": "dense pile (workload 3's generator in a 1.8 m pen)", "towers": "towers of boxes (A.7)"}[args.workload]
-    params = dict(params, batch_size=args.batch_size)
+    params = dict(params, batch_size=args.batch_size, sweep_order=1 if args.sweep_order == "levels" else 0)
     dev = torch.device("cuda:0")
     words = torch.from_numpy(k2d.pack_scenes(caps, scene).view(np.int32)).to(dev)
     actions = torch.from_numpy(actions_h).to(dev)
@@ -191,7 +194,8 @@ def main():
     kern_avg = float(np.mean(kern_ms)) * 1e-3
     achieved = flops_step * env_steps / kern_avg / 1e12
     executed = flops_exec * env_steps / kern_avg / 1e12
-    traffic, traffic_at = read_traffic(cfg["name"]) if (args.batch_size == 0 and args.workload == "config") else (None, None)
+    traffic, traffic_at = read_traffic(cfg["name"]) if (args.batch_size == 0 and args.workload == "config"
+                                                              and args.sweep_order == "tournament") else (None, None)
     out = {
         "metric": "physics env-steps/sec on 1 MI355X (%s scenes, %d envs)" % (cfg["name"], n_envs),
         "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -200,7 +204,9 @@ def main():
         "config": {"workload": "%s, %d envs x %d steps, %d substeps x %d solver sweeps, caps P/C/J/T=%s"
                    % (wl_name, n_envs, n_steps, params["n_substeps"], params["n_iters"], "/".join(map(str, caps))),
                    "env_steps_per_launch": env_steps, "seed": scenegen.SEED,
-                   "schedule": "sequential sweep, level after level" if args.batch_size == 0 else "batches of %d (A.8)" % args.batch_size},
+                   "schedule": ("sequential sweep, %s" % ("level after level" if args.sweep_order == "levels"
+                                                         else "tournament order")) if args.batch_size == 0
+                   else "batches of %d (A.8)" % args.batch_size},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / FP32_VALU_PEAK_TFLOPS, "traffic": traffic, "traffic_profiled_at": traffic_at,
                      "frac_nonpacked": achieved / FP32_VALU_PEAK_NONPACKED,

@@ -53,17 +53,26 @@ typedef struct {
   float joint_alpha;           /* A.4.1 velocity correction of the joint point constraint, 1/s         */
   float joint_beta;            /* A.4.1 positional correction of the joint point constraint            */
   float tie_eps;               /* A.3.4: b's face is the reference face only if it wins by tie_eps     */
-  int32_t batch_size;          /* A.8: 0 = collision constraints one after the other, level after level */
-                               /* (the colliding pairs are walked in the order of a round-robin         */
-                               /* tournament over the shapes; each takes the lowest level that no       */
-                               /* earlier colliding pair sharing a movable shape with it has taken; the */
-                               /* pairs of a level are independent and are solved at once, same bits);  */
+  int32_t batch_size;          /* A.8: 0 = collision constraints one after the other (sweep_order);     */
                                /* B in 1..K2D_MAX_BATCH_SIZE = the manifold points, two per pair in     */
                                /* tournament order, dealt in turn over ceil(points / B) batches; a      */
                                /* batch is solved from the velocities it starts with and its impulses   */
                                /* applied in point order (16 in the paper)                              */
+  int32_t sweep_order;         /* A.8 leaves the order of the active collision constraints to the       */
+                               /* engine.  K2D_SWEEP_TOURNAMENT (0): the order of a round-robin         */
+                               /* tournament over the shapes (round r pairs (m-1, r) and ((r+k) mod     */
+                               /* (m-1), (r-k) mod (m-1)), m = N rounded up to even).                   */
+                               /* K2D_SWEEP_LEVELS (1): the colliding pairs are walked in that order,   */
+                               /* each takes the lowest level that no earlier colliding pair sharing a  */
+                               /* movable shape with it has taken, and the sweep visits level 0, then   */
+                               /* level 1, ...: fewer dependent steps on piles and stacks.  Both are    */
+                               /* sequential sweeps; pairs without a common movable shape are solved    */
+                               /* side by side, which changes no bit.  Warm start and positional        */
+                               /* corrections follow the same order.                                    */
 } k2d_params;
 #define K2D_MAX_BATCH_SIZE 32
+#define K2D_SWEEP_TOURNAMENT 0
+#define K2D_SWEEP_LEVELS 1
 
 /* Word (4-byte) offsets inside one environment record.  A record is an array of 32-bit words, floats
  * unless marked (i) = int32.  Arrays are stored component-major ("structure of arrays" inside the

@@ -63,11 +63,13 @@ struct Params {
   double joint_alpha = 6.0;            // joint point-constraint velocity correction, 1/s (A.4.1)
   double joint_beta = 0.2;             // joint positional correction                     (A.4.1)
   double tie_eps = 1e-3;               // reference face goes to b only if sep_b > sep_a + tie_eps
-  int order_mode = 0;                  // 0: level after level (the visiting order below); 1: each level from a snapshot (test);
-                                       // 2: plain tournament order, no levels (comparison)
+  int order_mode = 0;                  // 0: one pair after the other; 1 (test): every group of the visiting order
+                                       // (a round, or a level) from one snapshot of the bodies
   int batch_size = 0;                  // 0: sequential sweep; B >= 1: batched impulse resolution (A.8)
+  int sweep_order = 0;                 // visiting order of the colliding pairs: 0 = tournament order,
+                                       // 1 = level after level (lowest free level), see substep()
 };
-constexpr int kNumParams = 17;
+constexpr int kNumParams = 18;
 
 template <class R>
 struct V2 {
@@ -210,14 +212,14 @@ struct Env {
   std::vector<Joint<R>> joints;
   std::vector<Thruster<R>> thrusters;
   std::vector<Manifold<R>> manifolds;  // lexicographic pair order
-  std::vector<int> pair_colour;        // lexicographic pair order: colour of the pair at the last substep, -1 = not colliding
+  std::vector<int> pair_level;         // lexicographic pair order: lowest free level of the pair at the last substep, -1 = not colliding
   std::vector<ContactAcc<R>> acc;      // lexicographic pair order
   double min_margin = std::numeric_limits<double>::infinity();
   // work counters, summed over substeps (they feed the benchmark's count of arithmetic, nothing else)
   int n_active_slots_sum = 0;          // active manifold points
   int n_active_pairs_sum = 0;          // pairs with at least one active point
   int n_pp_overlap_sum = 0;            // polygon pairs that went past the separating-axis test
-  int n_colours_sum = 0;               // colours (independent sets) of the colliding pairs, summed over substeps
+  int n_levels_sum = 0;                // levels (independent sets) of the colliding pairs, summed over substeps
   int n_substeps_done = 0;
 };
 
@@ -718,43 +720,43 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
 
   // -- Visiting order of the colliding pairs (A.8).  The paper solves constraints one after the other
   //    where it can afford to, and leaves the order of the active manifolds to the engine (its own
-  //    spreads them over its batches).  Here: walk the colliding pairs in tournament order and give
-  //    each the lowest level that no earlier colliding pair sharing a movable shape with it has taken;
-  //    visit level 0 first, then level 1, ..., tournament order inside a level.  Pairs of one level
-  //    share no shape that an impulse can move, so a level is a set of independent constraints and the
-  //    sweep stays a sequential (Gauss-Seidel) one, as short as the busiest shape's contacts allow.
-  //    Shapes that no impulse moves (inactive, or neither inverse mass nor inverse inertia) tie nothing
-  //    together.
+  //    spreads them over its batches).  Two orders are built here, both sequential (Gauss-Seidel):
+  //    sweep_order 0: the tournament order itself.  Its groups are the rounds (disjoint shapes).
+  //    sweep_order 1: walk the colliding pairs in tournament order and give each the lowest level that
+  //      no earlier colliding pair sharing a movable shape with it has taken; visit level 0 first, then
+  //      level 1, ..., tournament order inside a level.  Pairs of one level share no shape that an
+  //      impulse can move, so a level is a set of independent constraints, and the sweep is as short as
+  //      the busiest shape's contacts allow.  Shapes that no impulse moves (inactive, or neither inverse
+  //      mass nor inverse inertia) tie nothing together.
   std::vector<int> visit;            // indices into cps, in visiting order
-  std::vector<int> colour_end;       // visit[colour_end[c-1] .. colour_end[c]) is colour c
+  std::vector<int> group_end;        // visit[group_end[g-1] .. group_end[g]) is group g (a round, or a level)
   {
     auto movable = [&](int i) {
       const Body<R>& s = E.bodies[i];
       return s.active && (s.inv_mass != R(0) || s.inv_inertia != R(0));
     };
-    std::vector<unsigned> taken(N, 0u);   // colours already used at each movable shape
-    std::vector<int> colour(cps.size(), -1);
-    int n_colours = 0;
+    std::vector<unsigned> taken(N, 0u);   // levels already used at each movable shape
+    std::vector<int> group(cps.size(), -1);
+    int n_groups = 0, n_levels = 0;
     for (size_t q = 0; q < cps.size(); ++q) {
-      E.pair_colour[pair_index(cps[q].a, cps[q].b, N)] = -1;
+      E.pair_level[pair_index(cps[q].a, cps[q].b, N)] = -1;
       if (!cps[q].any) continue;
-      int c = 0;
-      if (P.order_mode != 2) {
-        unsigned busy = (movable(cps[q].a) ? taken[cps[q].a] : 0u) | (movable(cps[q].b) ? taken[cps[q].b] : 0u);
-        while ((busy >> c) & 1u) ++c;
-        if (movable(cps[q].a)) taken[cps[q].a] |= 1u << c;
-        if (movable(cps[q].b)) taken[cps[q].b] |= 1u << c;
-      }
-      colour[q] = c;
-      E.pair_colour[pair_index(cps[q].a, cps[q].b, N)] = c;
-      n_colours = std::max(n_colours, c + 1);
+      unsigned busy = (movable(cps[q].a) ? taken[cps[q].a] : 0u) | (movable(cps[q].b) ? taken[cps[q].b] : 0u);
+      int lv = 0;
+      while ((busy >> lv) & 1u) ++lv;
+      if (movable(cps[q].a)) taken[cps[q].a] |= 1u << lv;
+      if (movable(cps[q].b)) taken[cps[q].b] |= 1u << lv;
+      E.pair_level[pair_index(cps[q].a, cps[q].b, N)] = lv;
+      n_levels = std::max(n_levels, lv + 1);
+      group[q] = P.sweep_order == 1 ? lv : S.round[q];
+      n_groups = std::max(n_groups, group[q] + 1);
     }
-    for (int c = 0; c < n_colours; ++c) {
+    for (int g = 0; g < n_groups; ++g) {
       for (size_t q = 0; q < cps.size(); ++q)
-        if (colour[q] == c) visit.push_back((int)q);
-      colour_end.push_back((int)visit.size());
+        if (group[q] == g) visit.push_back((int)q);
+      group_end.push_back((int)visit.size());
     }
-    E.n_colours_sum += n_colours;
+    E.n_levels_sum += n_levels;
   }
 
   // -- Warm starting (Alg. 1; A.7): collisions in visiting order, then joints in index order -------
@@ -792,11 +794,11 @@ void substep(Env<R>& E, const Params& P, const Schedule& S, int nP, const double
     } else if (P.order_mode != 1) {
       for (int q : visit) solve_contact_pair(E, cps[q], E.acc[pair_index(cps[q].a, cps[q].b, N)]);
     } else {
-      // test mode: every pair of a colour starts from the same snapshot of the bodies and only what it
-      // did to its own two bodies is kept (for a shape that no impulse moves that is nothing) -- equal
-      // to the sequential sweep iff the pairs of a colour share no movable shape
+      // test mode: every pair of a group (round or level) starts from the same snapshot of the bodies and
+      // only what it did to its own two bodies is kept -- equal to the sequential sweep iff the pairs of a
+      // group share no shape that an impulse moves
       int z0 = 0;
-      for (int z1 : colour_end) {
+      for (int z1 : group_end) {
         std::vector<Body<R>> snap = E.bodies, out = E.bodies;
         for (int z = z0; z < z1; ++z) {
           ContactPair<R>& cp = cps[visit[z]];
@@ -874,7 +876,7 @@ struct Batch : BatchBase {
       e.joints.resize(J);
       e.thrusters.resize(T);
       e.manifolds.resize(NP);
-      e.pair_colour.assign(NP, -1);
+      e.pair_level.assign(NP, -1);
       e.acc.resize(NP);
     }
   }
@@ -936,13 +938,13 @@ struct Batch : BatchBase {
     FIELD("manifold_pen", NP * 2, e.manifolds[i / 2].pen[i % 2], RR)
     FIELD("manifold_normal", NP * 2, (i % 2 ? e.manifolds[i / 2].normal.y : e.manifolds[i / 2].normal.x), RR)
     FIELD("manifold_pos", NP * 4, (i % 2 ? e.manifolds[i / 4].pos[(i / 2) % 2].y : e.manifolds[i / 4].pos[(i / 2) % 2].x), RR)
-    FIELD("pair_colour", NP, e.pair_colour[i], II)
+    FIELD("pair_level", NP, e.pair_level[i], II)
     FIELD("pair_margin", NP, e.manifolds[i].margin, double)
     FIELD("min_margin", 1, e.min_margin, double)
     FIELD("active_slots_sum", 1, e.n_active_slots_sum, II)
     FIELD("active_pairs_sum", 1, e.n_active_pairs_sum, II)
     FIELD("pp_overlap_sum", 1, e.n_pp_overlap_sum, II)
-    FIELD("colours_sum", 1, e.n_colours_sum, II)
+    FIELD("levels_sum", 1, e.n_levels_sum, II)
     FIELD("substeps_done", 1, e.n_substeps_done, II)
 #undef FIELD
 #undef RR
@@ -1100,7 +1102,7 @@ void ko_destroy(void* h) { delete static_cast<BatchBase*>(h); }
 
 // params: [dt, gravity_y, n_substeps, n_iters, warm_start, alpha, beta, gamma, rho, slop,
 //          restitution_threshold, clip_thruster_01, joint_alpha, joint_beta, tie_eps, order_mode,
-//          batch_size]
+//          batch_size, sweep_order]
 int ko_set_params(void* h, const double* p, int n) {
   if (!h || !p || n != kNumParams) return -1;
   Params& q = static_cast<BatchBase*>(h)->params;
@@ -1108,8 +1110,8 @@ int ko_set_params(void* h, const double* p, int n) {
   q.alpha = p[5]; q.beta = p[6]; q.gamma = p[7]; q.rho = p[8]; q.slop = p[9];
   q.restitution_threshold = p[10]; q.clip_thruster_01 = (int)p[11];
   q.joint_alpha = p[12]; q.joint_beta = p[13]; q.tie_eps = p[14]; q.order_mode = (int)p[15];
-  q.batch_size = (int)p[16];
-  if (q.n_substeps < 1 || q.n_iters < 0 || q.batch_size < 0) return -2;
+  q.batch_size = (int)p[16]; q.sweep_order = (int)p[17];
+  if (q.n_substeps < 1 || q.n_iters < 0 || q.batch_size < 0 || q.sweep_order < 0 || q.sweep_order > 1) return -2;
   return 0;
 }
 long ko_field_size(void* h, const char* f) { return static_cast<BatchBase*>(h)->field_size(f); }

@@ -16,7 +16,7 @@ _LIB = os.path.join(_HERE, "libk2d_oracle.so")
 
 PARAM_ORDER = ["dt", "gravity_y", "n_substeps", "n_iters", "warm_start", "alpha", "beta", "gamma", "rho",
                "slop", "restitution_threshold", "clip_thruster_01", "joint_alpha", "joint_beta", "tie_eps",
-               "order_mode", "batch_size"]
+               "order_mode", "batch_size", "sweep_order"]
 
 # Fields a scene description may carry (see k2d_oracle.cpp, Batch::find).
 SCENE_FIELDS = ["pos", "theta", "vel", "omega", "inv_mass", "inv_inertia", "friction", "restitution", "density",
@@ -115,6 +115,7 @@ class Oracle:
         p = dict(params)
         p.setdefault("order_mode", 0)
         p.setdefault("batch_size", 0)
+        p.setdefault("sweep_order", 0)
         v = _f64([p[k] for k in PARAM_ORDER])
         rc = lib().ko_set_params(self._h, _dptr(v), len(v))
         if rc:

@@ -26,7 +26,8 @@ class k2d_params(ctypes.Structure):
                 ("beta", ctypes.c_float), ("gamma", ctypes.c_float), ("rho", ctypes.c_float),
                 ("slop", ctypes.c_float), ("restitution_threshold", ctypes.c_float),
                 ("clip_thruster_01", ctypes.c_int32), ("joint_alpha", ctypes.c_float),
-                ("joint_beta", ctypes.c_float), ("tie_eps", ctypes.c_float), ("batch_size", ctypes.c_int32)]
+                ("joint_beta", ctypes.c_float), ("tie_eps", ctypes.c_float), ("batch_size", ctypes.c_int32),
+                ("sweep_order", ctypes.c_int32)]
 
 
 _LAYOUT_FIELDS = ["n_shapes", "n_pairs", "pos_x", "pos_y", "theta", "vel_x", "vel_y", "omega", "inv_mass",
@@ -107,7 +108,9 @@ def make_caps(caps):
 def make_params(p):
     p = dict(p)
     p.setdefault("batch_size", 0)
-    return k2d_params(**{k: (int(p[k]) if k in ("n_substeps", "n_iters", "warm_start", "clip_thruster_01", "batch_size")
+    p.setdefault("sweep_order", 0)
+    return k2d_params(**{k: (int(p[k]) if k in ("n_substeps", "n_iters", "warm_start", "clip_thruster_01", "batch_size",
+                                                "sweep_order")
                              else float(p[k])) for k, _ in k2d_params._fields_})
 
 

@@ -17,13 +17,14 @@
 //     deeper than registers and LDS hold, and for the new scenes of restarted episodes.  Lanes of a group
 //     exchange body velocities through LDS.
 //   * The sweep order of the collision constraints (A.8 leaves it to the engine) is built from a
-//     round-robin tournament over the shapes, whose rounds touch disjoint shapes: walking the colliding
-//     pairs in that order, a pair takes the lowest level that no earlier colliding pair sharing a movable
-//     shape with it has taken, and the sweep visits level after level.  The pairs of a level are
-//     independent, so all of them are solved at once and the result is bit-identical to a sequential
-//     Gauss-Seidel sweep in that order (the sequential end of the speed/stability trade-off of A.8,
-//     reached without the paper's batch-of-16 compromise), in about as many trips as the busiest shape
-//     has contacts.
+//     round-robin tournament over the shapes, whose rounds touch disjoint shapes.  Walking the colliding
+//     pairs in that order, a pair is placed on a level that none of the earlier colliding pairs sharing a
+//     movable shape with it is on: one past the last of them (the sweep then has the bits of visiting the
+//     pairs one after the other in tournament order), or, as an option, the lowest free one (the sweep
+//     then visits level after level, in about as many trips as the busiest shape has contacts).  The
+//     pairs of a level are independent, all of them are solved at once, and the result is bit-identical
+//     to a sequential Gauss-Seidel sweep (the sequential end of the speed/stability trade-off of A.8,
+//     reached without the paper's batch-of-16 compromise).
 //   * Active manifolds of a substep become records that live in registers: lane k of the environment
 //     keeps active pairs k and G + k for the whole substep (warm start, all sweeps, corrections), so a
 //     visit costs one LDS round trip for the two bodies' velocities and nothing else; the accumulated
@@ -195,6 +196,7 @@ struct Params {   // device copy of k2d_params with the substep precomputed
   int clip_thr;
   float joint_alpha, joint_beta, tie_eps;
   int n_batches;   // batched schedule (A.8): batches per sweep of the collision constraints, 0 = not used
+  int lowest_free_level;   // visiting order of the colliding pairs: 0 = tournament order, 1 = level after level
 };
 
 __device__ __forceinline__ int f2i(float f) { return __float_as_int(f); }
@@ -1149,16 +1151,19 @@ __global__ void __launch_bounds__(64, K::EPW == 4 ? 2 : 1) k2d_step_kernel(float
       }
       wave_sync();
       K2D_T(kT_Presolve);
-      // Levels of the active pairs: the visiting order of the sweep (A.8 leaves the order of the active
-      // constraints to the engine).  Walking the colliding pairs in tournament order (round by round), a
-      // pair takes the lowest level that no earlier colliding pair sharing a movable shape with it has
-      // taken; the sweep visits level 0, then level 1, ...  Pairs of one level touch disjoint movable
-      // shapes, so solving a level at once gives the same bits as visiting its pairs one after the
-      // other: the sweep is a sequential one, in as few trips as the busiest shape has contacts (or one
-      // more; everything resting on the static floor is one level; a level never exceeds the round).
-      // The lane that tests a pair also places it: the pairs of a round touch disjoint shapes, so the
-      // lanes of a round read and extend the sets of levels taken at their two shapes (16-bit words in
-      // LDS) without getting in each other's way, and the rounds follow one another.
+      // Levels of the active pairs.  The colliding pairs are walked in tournament order (round by round).
+      // k2d_params.sweep_order = K2D_SWEEP_TOURNAMENT: the sweep visits them in that order, and a pair is
+      // placed one level after the last earlier colliding pair that shares a movable shape with it --
+      // pairs that share one keep their order, so sweeping the levels in turn, each level at once, gives
+      // the same bits as the one-after-the-other sweep in tournament order.
+      // K2D_SWEEP_LEVELS: a pair takes the lowest level that no earlier colliding pair sharing a movable
+      // shape with it has taken, and the sweep's order *is* level 0, then level 1, ...: as few trips as
+      // the busiest shape has contacts (or one more).
+      // Either way the pairs of a level touch disjoint movable shapes, everything resting on the static
+      // floor is one level, and a level never exceeds the round.  The lane that tests a pair also places
+      // it: the pairs of a round touch disjoint shapes, so the lanes of a round read and extend the sets
+      // of levels taken at their two shapes (16-bit words in LDS) without getting in each other's way,
+      // and the rounds follow one another.
       if (!levels_valid || __any(set_changed)) {
         if (k < (N + 1) / 2) reinterpret_cast<unsigned*>(taken)[k] = 0u;
         wave_sync();
@@ -1174,7 +1179,7 @@ __global__ void __launch_bounds__(64, K::EPW == 4 ? 2 : 1) k2d_step_kernel(float
               const int a = pk & 15, b = pk >> 4;
               const bool ma = !((static_mask >> a) & 1u), mb = !((static_mask >> b) & 1u);
               const unsigned ta = ma ? (unsigned)taken[a] : 0u, tb = mb ? (unsigned)taken[b] : 0u;
-              const int lv = __ffs((int)~(ta | tb)) - 1;
+              const int lv = prm.lowest_free_level ? __ffs((int)~(ta | tb)) - 1 : 32 - __clz((int)(ta | tb));
               if (ma) taken[a] = (unsigned short)(ta | (1u << lv));
               if (mb) taken[b] = (unsigned short)(tb | (1u << lv));
               lvl[r * GP + kp] = (unsigned char)lv;
@@ -2093,6 +2098,7 @@ static Params device_params(const k2d_params& p) {
   prm.clip_thr = p.clip_thruster_01;
   prm.joint_alpha = p.joint_alpha; prm.joint_beta = p.joint_beta; prm.tie_eps = p.tie_eps;
   prm.n_batches = 0;
+  prm.lowest_free_level = p.sweep_order == K2D_SWEEP_LEVELS;
   return prm;
 }
 
@@ -2189,6 +2195,7 @@ int k2d_alloc_batch(const k2d_caps* caps, const k2d_params* params, int n_envs, 
   if (cls < 0) return K2D_E_CAP;
   if (params->n_substeps < 1 || params->n_iters < 0 || !(params->dt > 0.f)) return K2D_E_ARG;
   if (params->batch_size < 0 || params->batch_size > K2D_MAX_BATCH_SIZE) return K2D_E_ARG;
+  if (params->sweep_order != K2D_SWEEP_TOURNAMENT && params->sweep_order != K2D_SWEEP_LEVELS) return K2D_E_ARG;
   if (state_bytes < k2d_state_bytes(caps, n_envs)) return K2D_E_SIZE;
   k2d_batch* b = new (std::nothrow) k2d_batch;
   if (!b) return K2D_E_ARG;

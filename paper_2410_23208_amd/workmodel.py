@@ -156,9 +156,9 @@ I_JOINT_WARM = 12
 def sequential_chain_instructions(caps, scene, params, pair_points, schedule):
     """Length, in instructions, of the chain of constraint visits that the sweep order forces to run one
     after the other in one substep of every environment: constraints that share a movable shape keep their
-    order (joints in index order; collisions level after level, a pair taking the lowest level that no
-    earlier colliding pair of the tournament order sharing a movable shape with it has; Algorithm 1 and A.8),
-    the others may run side by side.  pair_points [E, n_pairs] = active manifold points per pair
+    order (joints in index order; collisions in tournament order, or -- params["sweep_order"] = 1 -- level
+    after level, a pair taking the lowest level that no earlier colliding pair of the tournament order sharing
+    a movable shape with it has; Algorithm 1 and A.8), the others may run side by side.  pair_points [E, n_pairs] = active manifold points per pair
     (lexicographic pair order) of a sampled substep; schedule = (a[], b[]) tournament order.  A visit of a pair costs its points one
     after the other; a level costs its longest visit.  Returns an array [E]: instructions per substep for
     warm starting plus `n_iters` sweeps -- at best one instruction every four clocks on one wavefront."""
@@ -192,9 +192,12 @@ def sequential_chain_instructions(caps, scene, params, pair_points, schedule):
             if npt == 0:
                 continue
             busy = (taken[a] if movable[e, a] else 0) | (taken[b] if movable[e, b] else 0)
-            lv = 0
-            while (busy >> lv) & 1:
-                lv += 1
+            if params.get("sweep_order", 0) == 1:      # level order: the lowest free level
+                lv = 0
+                while (busy >> lv) & 1:
+                    lv += 1
+            else:                                      # tournament order: one past the last pair it must wait for
+                lv = busy.bit_length()
             pl_pts[lv] = max(pl_pts.get(lv, 0), npt)
             if movable[e, a]:
                 taken[a] |= 1 << lv

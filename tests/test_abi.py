@@ -60,6 +60,9 @@ def test_argument_errors_without_device_work():
     for bad_b in (-1, 33):                                                        # batches of 0 (off) .. 32 points
         prm_b = binding.make_params(dict(scenegen.default_params(), batch_size=bad_b))
         assert lib.k2d_alloc_batch(ctypes.byref(caps), ctypes.byref(prm_b), 4, fake, 1 << 20, ctypes.byref(h)) == -1
+    for bad_o in (-1, 2):                                                         # the two visiting orders of the sweep
+        prm_o = binding.make_params(dict(scenegen.default_params(), sweep_order=bad_o))
+        assert lib.k2d_alloc_batch(ctypes.byref(caps), ctypes.byref(prm_o), 4, fake, 1 << 20, ctypes.byref(h)) == -1
     assert lib.k2d_alloc_batch(ctypes.byref(caps), ctypes.byref(prm), 4, fake, 1 << 20, ctypes.byref(h)) == 0
     assert lib.k2d_set_lanes_per_env(h, 8) == 0 and lib.k2d_set_lanes_per_env(h, 16) == 0
     assert lib.k2d_set_lanes_per_env(h, 4) == -1 and lib.k2d_set_lanes_per_env(None, 8) == -1

@@ -95,9 +95,31 @@ def test_eight_lanes_dense_pile_and_pool_overflow():
     assert ((os_["pair_count"] > 0).sum(1) > 16).any()
 
 
-def test_stacking_workload_bit_identical():
-    """Towers of up to nine boxes: dependency chains as long as a tower is high."""
+@pytest.mark.parametrize("cfg,n,steps,lanes", [(0, 67, 120, 0), (1, 131, 64, 0), (2, 259, 64, 0), (3, 131, 96, 0),
+                                               (4, 195, 64, 0), (3, 131, 48, 8), (0, 131, 64, 8)])
+def test_level_order_of_the_sweep_bit_identical(cfg, n, steps, lanes):
+    """k2d_params.sweep_order = K2D_SWEEP_LEVELS (the colliding pairs visited level after level, each on the
+    lowest level free at its movable shapes) against the oracle sweeping in the same order -- and the result
+    differs from the tournament order's wherever a shape has several contacts."""
+    caps, prm, sc = scenegen.make_scene(cfg, n_envs=n)
+    prm = dict(prm, sweep_order=1)
+    act = scenegen.make_actions(cfg, steps, n)
+    o = parity.run_oracle(caps, prm, sc, act)
+    b = parity.run_gpu(caps, prm, sc, act, lanes=lanes)
+    gs, os_ = b.state_dict(), o.state()
+    for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+        assert np.array_equal(gs[k], os_[k]), k
+    if cfg in (2, 3):
+        other = parity.run_oracle(caps, dict(prm, sweep_order=0), sc, act).state()
+        assert not np.array_equal(other["vel"], os_["vel"])
+
+
+@pytest.mark.parametrize("sweep_order", [0, 1])
+def test_stacking_workload_bit_identical(sweep_order):
+    """Towers of up to nine boxes: chains of contacts, which the tournament order walks in as many dependent
+    steps as a tower is high and the level order in three."""
     caps, prm, sc = scenegen.make_stack_scene(n_envs=131)
+    prm = dict(prm, sweep_order=sweep_order)
     act = np.zeros((96, 131, caps[2] + caps[3]), dtype=np.float32)
     o = parity.run_oracle(caps, prm, sc, act)
     b = parity.run_gpu(caps, prm, sc, act)
@@ -107,10 +129,12 @@ def test_stacking_workload_bit_identical():
     assert ((os_["pair_count"] > 0).sum(1) == 13).all()
 
 
-def test_dense_pile_workload_bit_identical():
+@pytest.mark.parametrize("sweep_order", [0, 1])
+def test_dense_pile_workload_bit_identical(sweep_order):
     """Workload 3's heap in a narrow pen: many environments keep more colliding pairs than one per lane, so the
     second register-held pair of a lane is exercised over several wavefronts."""
     caps, prm, sc = scenegen.make_dense_scene(n_envs=195)
+    prm = dict(prm, sweep_order=sweep_order)
     act = scenegen.make_actions(3, 96, 195)
     o = parity.run_oracle(caps, prm, sc, act)
     b = parity.run_gpu(caps, prm, sc, act)
@@ -370,8 +394,9 @@ def test_single_environment_and_empty_scene():
     assert os_["pair_count"].sum() >= 2
 
 
-@pytest.mark.parametrize("B,lanes", [(0, 0), (16, 0), (32, 0), (3, 0), (0, 8), (16, 8)])
-def test_pile_deeper_than_the_lds_pool(B, lanes):
+@pytest.mark.parametrize("B,lanes,sweep_order", [(0, 0, 0), (16, 0, 0), (32, 0, 0), (3, 0, 0), (0, 8, 0), (16, 8, 0),
+                                                 (0, 0, 1), (16, 0, 1), (0, 8, 1)])
+def test_pile_deeper_than_the_lds_pool(B, lanes, sweep_order):
     """All 16 shapes of an L scene dumped onto one spot: far more active pairs than the per-environment
     LDS pool holds, so the overflow path through the HBM record is exercised (under both schedules)."""
     caps = scenegen.CAPS["L"]
@@ -383,7 +408,8 @@ def test_pile_deeper_than_the_lds_pool(B, lanes):
             sb.box(0.3 + 0.02 * k, 0.25, (0.05 * k + 0.01 * e, 0.5 + 0.04 * k), theta=0.1 * k, friction=0.4, e=e)
         for k in range(4):
             sb.circle(0.3, (0.1 * k, 0.6 + 0.05 * k), e=e)
-    prm = mkparams(n_substeps=3, n_iters=10, alpha=0.5, beta=0.02, batch_size=B)   # gentle corrections: the pile persists
+    prm = mkparams(n_substeps=3, n_iters=10, alpha=0.5, beta=0.02, batch_size=B,    # gentle corrections: the pile persists
+                   sweep_order=sweep_order)
     sc = sb.scene()
     act = np.zeros((6, 3, caps[2] + caps[3]), dtype=np.float32)
     o = parity.run_oracle(caps, prm, sc, act)

@@ -477,10 +477,10 @@ def _visiting_order(N, colliding, movable):
 
 @pytest.mark.parametrize("workload", ["config 3", "dense pile", "towers"])
 def test_visiting_order_is_the_lowest_free_level_walk_of_the_tournament_order(workload):
-    """The order of the sweep over the colliding pairs (A.8 leaves it to the engine): the oracle's levels equal
-    the ones worked out here from the colliding set alone; pairs of one level share no movable shape; a level is
-    never later than the place the pair would have one past its last conflicting predecessor, and on piles it
-    is often earlier."""
+    """The level-after-level order of the sweep (sweep_order = 1; A.8 leaves the order to the engine): the oracle's
+    levels equal the ones worked out here from the colliding set alone; pairs of one level share no movable shape; a
+    level is never later than the place the pair would have one past its last conflicting predecessor, and on
+    piles it is often earlier."""
     n = 16
     if workload == "config 3":
         caps, p, sc = scenegen.make_scene(3, n_envs=n)
@@ -492,10 +492,10 @@ def test_visiting_order_is_the_lowest_free_level_walk_of_the_tournament_order(wo
         caps, p, sc = scenegen.make_stack_scene(n_envs=n)
         act = np.zeros((20, n, caps[2] + caps[3]))
     N = caps[0] + caps[1]
-    o = Oracle(caps, n, p, "f32")
+    o = Oracle(caps, n, dict(p, sweep_order=1), "f32")
     o.load_scene(sc)
     o.step(act)
-    colour = o.get("pair_colour").reshape(n, -1)
+    colour = o.get("pair_level").reshape(n, -1)
     active = o.get("pair_active").reshape(n, -1, 2).any(-1)
     earlier = 0
     for e in range(n):
@@ -516,8 +516,8 @@ def test_visiting_order_is_the_lowest_free_level_walk_of_the_tournament_order(wo
 def test_sweep_visits_the_levels_in_order_closed_form():
     """Four equal frictionless balls in a row, no gravity, no restitution, one sweep: a colliding pair that
     approaches ends at the mean of its two velocities.  The outcome depends on the order of the three contacts;
-    the oracle's equals the one worked out here for the level-by-level order (the outer contacts, then the
-    middle one) and, with the plain tournament order switched on, the one for that order."""
+    under sweep_order = 1 the oracle's equals the one worked out here for the level-by-level order (the outer
+    contacts, then the middle one), under sweep_order = 0 the one for the tournament order."""
     caps = (1, 4, 1, 1)
     N, r, pen = 5, 0.5, 1e-4
     a, b, _ = ko.schedule(N)
@@ -543,7 +543,7 @@ def test_sweep_visits_the_levels_in_order_closed_form():
     level, _ = _visiting_order(N, contacts, lambda i: True)
     by_level = sorted(walk, key=lambda pr: (level[pr], walk.index(pr)))
     assert by_level != walk and expected(by_level) != expected(walk)
-    for mode, order in ((0, by_level), (2, walk)):
+    for sweep_order, order in ((1, by_level), (0, walk)):
         sb = SceneBuilder(caps)
         ids = {}
         for k in range(4):
@@ -551,7 +551,7 @@ def test_sweep_visits_the_levels_in_order_closed_form():
         for q, s in enumerate(place):
             sb.sc["pos"][0, s] = (q * (2 * r - pen), 3.0)
             sb.sc["vel"][0, s] = (v0[s], 0.0)
-        o, _ = run(sb, params(n_iters=1, gravity_y=0.0, warm_start=0, order_mode=mode), caps=caps)
+        o, _ = run(sb, params(n_iters=1, gravity_y=0.0, warm_start=0, sweep_order=sweep_order), caps=caps)
         o.step(zeros_actions(1, 1, caps))
         vel = o.state()["vel"].reshape(-1, 2)
         want = expected(order)
@@ -559,20 +559,44 @@ def test_sweep_visits_the_levels_in_order_closed_form():
             assert vel[s, 0] == pytest.approx(want[s], abs=1e-12) and vel[s, 1] == 0.0
 
 
-def test_level_at_once_equals_sequential_sweep():
-    """Solving every pair of a level from the same snapshot gives bit-identical results to visiting them one
-    after the other: the levels of the visiting order are conflict-free."""
+@pytest.mark.parametrize("sweep_order", [0, 1])
+def test_group_at_once_equals_sequential_sweep(sweep_order):
+    """Solving every pair of a round (tournament order) or of a level (level order) from the same snapshot
+    gives bit-identical results to visiting them one after the other: the groups of both visiting orders are
+    conflict-free."""
     caps, p, sc = scenegen.make_scene(3, n_envs=24)
     act = scenegen.make_actions(3, 40, 24)
     out = []
     for mode in (0, 1):
-        o = Oracle(caps, 24, dict(p, order_mode=mode), "f32")
+        o = Oracle(caps, 24, dict(p, order_mode=mode, sweep_order=sweep_order), "f32")
         o.load_scene(sc)
         o.step(act)
         out.append(o.state())
     assert out[0]["pair_count"].sum() > 24 * 3
     for k in ("pos", "theta", "vel", "omega", "lambda_n", "lambda_t", "joint_acc", "pair_count"):
         assert np.array_equal(out[0][k], out[1][k]), k
+
+
+def test_the_two_visiting_orders_differ_in_bits_and_agree_in_behaviour():
+    """Tournament order and level order are two sequential sweeps: different bits on a pile, the same physics --
+    the towers of boxes stand under both (millimetres of drift, the same settling)."""
+    caps, prm, sc = scenegen.make_stack_scene(n_envs=24)
+    act = np.zeros((256, 24, caps[2] + caps[3]))
+    p0 = np.asarray(sc["pos"])[:, 3:12]
+    res = []
+    for so in (0, 1):
+        o = Oracle(caps, 24, dict(prm, sweep_order=so), "f32")
+        o.load_scene(sc)
+        o.step(act, n_threads=4)
+        st = o.state()
+        pos = st["pos"].reshape(24, -1, 2)[:, 3:12]
+        res.append((st["pos"].copy(), np.abs(pos[..., 0] - p0[..., 0]).max(), (p0[..., 1] - pos[..., 1]).max(),
+                    np.abs(st["vel"]).max(), o.get("levels_sum")[:, 0].mean() / (256 * prm["n_substeps"])))
+    assert not np.array_equal(res[0][0], res[1][0])
+    for _, dx, dy, v, _ in res:
+        assert dx < 0.01 and 0.0 < dy < 0.03 and v < 0.02
+    assert abs(res[0][2] - res[1][2]) < 2e-3
+    assert res[1][4] <= 3.0          # a tower's contacts alternate between two levels, its foot takes a third
 
 
 def test_deterministic_and_thread_count_invariant():
@@ -775,8 +799,8 @@ def test_batch_size_one_is_the_sequential_sweep():
     caps, p, sc = scenegen.make_scene(3, n_envs=16)
     act = scenegen.make_actions(3, 30, 16)
     out = []
-    for B in (0, 1, 16):       # (the batches walk the plain tournament order: compared with the sweep in that order)
-        o = Oracle(caps, 16, dict(p, batch_size=B, order_mode=2), "f32")
+    for B in (0, 1, 16):
+        o = Oracle(caps, 16, dict(p, batch_size=B), "f32")
         o.load_scene(sc)
         o.step(act)
         out.append(o.state())
