@@ -5,6 +5,7 @@ the wavefronts' clocks and the clocks per wavefront-substep -- for all wavefront
 ones a launch of resident wavefronts waits for) and for the median eight.
 
   python -m paper_2410_23208_amd.phase_timers [--config 2] [--envs N] [--steps K] [--no-build] [--alone]
+                                              [--sweep-order tournament|levels]
 
 --alone: every environment of the workload in a wavefront of its own (three empty environments beside it, the
 ordering of the launch switched off), 2048 at a time: how long the chain of one environment is by itself --
@@ -32,6 +33,8 @@ def main():
     ap.add_argument("--steps", type=int, default=0)
     ap.add_argument("--no-build", action="store_true", help="use the libk2d_timers.so that is there")
     ap.add_argument("--alone", action="store_true", help="one environment per wavefront (see above)")
+    ap.add_argument("--sweep-order", default="tournament", choices=["tournament", "levels"],
+                    help="visiting order of the colliding pairs (k2d_params.sweep_order)")
     args = ap.parse_args()
     import torch          # first: the library must bind to the HIP runtime that torch has loaded
     import scenegen
@@ -44,6 +47,7 @@ def main():
     n_envs = args.envs or cfg["n_envs"]
     n_steps = args.steps or cfg["n_steps"]
     caps, params, scene = scenegen.make_scene(args.config, n_envs=n_envs)
+    params = dict(params, sweep_order=1 if args.sweep_order == "levels" else 0)
     act = torch.from_numpy(scenegen.make_actions(args.config, n_steps, n_envs)).cuda()
     words = torch.from_numpy(k2d.pack_scenes(caps, scene).view(np.int32)).cuda()
     if args.alone:
