@@ -35,6 +35,11 @@ ACC_FIELDS = ["joint_acc", "joint_acc_ang", "lambda_n", "lambda_t", "prev_active
 SANITIZE = os.environ.get("K2D_ORACLE_SANITIZE", "") not in ("", "0")
 if SANITIZE:
     _LIB = os.path.join(_HERE, "libk2d_oracle_san.so")
+# K2D_ORACLE_SOURCE=<file> builds and loads that source instead (the library is put beside it): how
+# oracle/mutation_check.py runs the pins against copies of the oracle with a mistake planted in each.
+if os.environ.get("K2D_ORACLE_SOURCE"):
+    _SRC = os.environ["K2D_ORACLE_SOURCE"]
+    _LIB = _SRC + ".so"
 
 
 def build(force=False):

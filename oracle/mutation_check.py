@@ -1,0 +1,126 @@
+#!/usr/bin/env python3
+"""How much the pins pin: plants one mistake at a time in a copy of the oracle (a dropped term, a wrong sign,
+a swapped operand, a wrong index, a transposed order) and runs the CPU test suite against the copy.  A mistake
+that no test notices is a gap in the pins.  CPU only; nothing here touches the GPU library.
+
+  python oracle/mutation_check.py [-j 4] [-k name-substring]
+
+Every entry: (name, text in k2d_oracle.cpp that must occur exactly once, replacement)."""
+import argparse
+import concurrent.futures as cf
+import os
+import subprocess
+import sys
+import tempfile
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+SRC = os.path.join(HERE, "k2d_oracle.cpp")
+
+MUTANTS = [
+    ("gravity sign", "b.vel.y = b.vel.y + R(P.gravity_y) * h;", "b.vel.y = b.vel.y - R(P.gravity_y) * h;"),
+    ("gravity on static shapes", "if (b.active && b.inv_mass > R(0)) b.vel.y", "if (b.active) b.vel.y"),
+    ("Euler step before the velocities", "    b.pos = b.pos + h * b.vel;\n", "    b.pos = b.pos + (h * R(0.5)) * b.vel;\n"),
+    ("Euler step forgets the rotation", "    b.theta = b.theta + h * b.omega;\n", "    b.theta = b.theta;\n"),
+    ("edge normal points inward", "wp.nrm[i] = {e.y / len, -e.x / len};", "wp.nrm[i] = {-e.y / len, e.x / len};"),
+    ("CC normal from b to a", "V2<R> d = pb - pa;\n  R L = std::sqrt(dot(d, d));", "V2<R> d = pa - pb;\n  R L = std::sqrt(dot(d, d));"),
+    ("CC penetration forgets a radius", "m.pen[0] = ra + rb - L;", "m.pen[0] = rb - L;"),
+    ("CC contact point on the wrong circle", "m.pos[0] = pa + ra * n;", "m.pos[0] = pb + ra * n;"),
+    ("PC projection not clipped to the segment", "t = std::min(std::max(t, R(0)), R(1));", "t = t;"),
+    ("PC penetration printed form r_b - |p| of the point", "m.pen[0] = rb - dist;", "m.pen[0] = rb - std::sqrt(dot(q, q));"),
+    ("PC inside case takes the wrong face", "if (s > smax) { ssecond = smax; smax = s; imax = i; }", "if (s > smax) { ssecond = smax; smax = s; imax = 0; }"),
+    ("PP face query takes the largest distance", "smin = std::min(smin, dot(X.nrm[i], Y.w[k] - X.w[i]));", "smin = std::max(smin == std::numeric_limits<R>::infinity() ? -smin : smin, dot(X.nrm[i], Y.w[k] - X.w[i]));"),
+    ("PP separating axis ignored", "if (std::max(sa, sb) >= R(0)) return;  // a separating axis exists: no collision", ""),
+    ("PP reference face always a", "bool ref_b = sb > sa + tie_eps;", "bool ref_b = false;"),
+    ("PP incident face most parallel", "if (d < dmin) { dsecond = dmin; dmin = d; jinc = j; }", "if (-d < dmin) { dsecond = dmin; dmin = -d; jinc = j; }"),
+    ("PP no clipping", "R uc = std::min(std::max(u[k], R(0)), len);", "R uc = u[k];"),
+    ("PP normal not flipped for reference b", "m.normal = ref_b ? V2<R>{-nref.x, -nref.y} : nref;", "m.normal = nref;"),
+    ("PP penetration sign", "m.pen[k] = -dot(nref, x - r1);", "m.pen[k] = dot(nref, x - r1);"),
+    ("impulse forgets the rotation", "b.omega = std::fma(b.inv_inertia, cross(r, j), b.omega);", "b.omega = b.omega;"),
+    ("relative velocity forgets w_b x r_b", "return {std::fma(b.omega, rb.y, std::fma(-a.omega, ra.y, a.vel.x) - b.vel.x),", "return {(std::fma(-a.omega, ra.y, a.vel.x) - b.vel.x),"),
+    ("normal impulse not clamped", "R ln = std::max(acc.lambda_n[k] + dl, R(0));", "R ln = acc.lambda_n[k] + dl;"),
+    ("restitution term dropped", "R dl = row.mass_n * (vn + row.rest + row.bias);", "R dl = row.mass_n * (vn + row.bias);"),
+    ("velocity correction dropped", "R dl = row.mass_n * (vn + row.rest + row.bias);", "R dl = row.mass_n * (vn + row.rest);"),
+    ("normal impulse on one body only", "  apply_impulse(b, V2<R>{-j.x, -j.y}, row.rb);\n  // friction impulse", "  // friction impulse"),
+    ("friction unclipped", "R lt = std::min(std::max(acc.lambda_t[k] + dt_, -lim), lim);", "R lt = acc.lambda_t[k] + dt_;"),
+    ("friction clip by the increment", "R lim = cp.mu * ln;", "R lim = cp.mu * dl;"),
+    ("friction along the normal", "R vt = dot(cp.t, rel_vel(a, row.ra, b, row.rb));", "R vt = dot(cp.n, rel_vel(a, row.ra, b, row.rb));"),
+    ("second manifold point never solved", "  for (int k = 0; k < 2; ++k)\n    if (cp.row[k].active) solve_contact_point(", "  for (int k = 0; k < 1; ++k)\n    if (cp.row[k].active) solve_contact_point("),
+    ("friction coefficient: mean instead of root of squares", "cp.mu = std::sqrt(a.friction * a.friction + b.friction * b.friction);", "cp.mu = (a.friction + b.friction) / R(2);"),
+    ("restitution: max instead of min", "cp.e = std::min(a.restitution, b.restitution);", "cp.e = std::max(a.restitution, b.restitution);"),
+    ("effective mass forgets the inertia of b", "R kn = a.inv_mass + b.inv_mass + ran * ran * a.inv_inertia + rbn * rbn * b.inv_inertia;", "R kn = a.inv_mass + b.inv_mass + ran * ran * a.inv_inertia;"),
+    ("lever arm of b from a's centre", "row.rb = m.pos[k] - b.pos;", "row.rb = m.pos[k] - a.pos;"),
+    ("slop ignored in the bias", "row.bias = R(P.alpha) * std::max(m.pen[k] - R(P.slop), R(0));", "row.bias = R(P.alpha) * std::max(m.pen[k], R(0));"),
+    ("accumulated impulses never wiped", "if (!(P.warm_start && row.active && acc.prev_active[k])) {", "if (!P.warm_start) {"),
+    ("restitution below the threshold", "row.rest = (vn0 > R(P.restitution_threshold)) ? cp.e * vn0 : R(0);", "row.rest = cp.e * vn0;"),
+    ("warm start applies the normal impulse with the wrong sign", "V2<R> j = (-acc.lambda_n[k]) * cp.n + acc.lambda_t[k] * cp.t;", "V2<R> j = (acc.lambda_n[k]) * cp.n + acc.lambda_t[k] * cp.t;"),
+    ("joined shapes collide", "joined[j.a * N + j.b] = joined[j.b * N + j.a] = 1;", "joined[j.a * N + j.b] = 0;"),
+    ("joint matrix off-diagonal sign", "jr.k12 = -a.inv_inertia * jr.ra.x * jr.ra.y - b.inv_inertia * jr.rb.x * jr.rb.y;", "jr.k12 = a.inv_inertia * jr.ra.x * jr.ra.y + b.inv_inertia * jr.rb.x * jr.rb.y;"),
+    ("joint solve transposed", "V2<R> j{(jr.k22 * rhs.x - jr.k12 * rhs.y) * jr.inv_det, (jr.k11 * rhs.y - jr.k12 * rhs.x) * jr.inv_det};", "V2<R> j{(jr.k11 * rhs.x - jr.k12 * rhs.y) * jr.inv_det, (jr.k22 * rhs.y - jr.k12 * rhs.x) * jr.inv_det};"),
+    ("joint anchors not rotated", "jr.ra = turn(a.theta, jt.anchor_a);", "jr.ra = jt.anchor_a;"),
+    ("joint velocity correction dropped", "jr.bias = R(P.joint_alpha) * sep;", "jr.bias = R(0) * sep;"),
+    ("fixed joint angular sign", "R d = -(a.omega - b.omega + jr.ang_bias) * jr.ang_mass;", "R d = (a.omega - b.omega + jr.ang_bias) * jr.ang_mass;"),
+    ("fixed joint forgets its rest angle", "jr.ang_bias = R(P.gamma) * (a.theta - b.theta - jt.theta_f);", "jr.ang_bias = R(P.gamma) * (a.theta - b.theta);"),
+    ("joint limit pushes while restoring", "if (!restoring) {", "if (true) {"),
+    ("joint limit: lower limit ignored", "else if (rel < jt.limit_lo) jr.lim_excess = rel - jt.limit_lo;", ""),
+    ("motor sign", "a.omega = a.omega - a.inv_inertia * motor[q];\n    b.omega = b.omega + b.inv_inertia * motor[q];", "a.omega = a.omega + a.inv_inertia * motor[q];\n    b.omega = b.omega - b.inv_inertia * motor[q];"),
+    ("motor without tanh", "motor[q] = jt.motor_power * Fn<R>::tanh(arg) * h;", "motor[q] = jt.motor_power * arg * h;"),
+    ("motors applied one after the other", "    motor[q] = jt.motor_power * Fn<R>::tanh(arg) * h;\n  }", "    motor[q] = jt.motor_power * Fn<R>::tanh(arg) * h;\n    E.bodies[jt.a].omega -= E.bodies[jt.a].inv_inertia * motor[q]; E.bodies[jt.b].omega += E.bodies[jt.b].inv_inertia * motor[q]; motor[q] = 0;\n  }"),
+    ("thruster at the centre of mass", "apply_impulse(b, imp, r);", "apply_impulse(b, imp, V2<R>{0, 0});"),
+    ("thruster direction not rotated with the body", "V2<R> dir = rotate(u.x, u.y, unit(th.angle));", "V2<R> dir = unit(th.angle);"),
+    ("positional correction shared equally", "a.pos = a.pos - (a.inv_mass * c) * cp.n;", "a.pos = a.pos - (b.inv_mass * c) * cp.n;"),
+    ("positional correction from the shallowest point", "for (int k = 0; k < 2; ++k) if (m.active[k]) pen = std::max(pen, m.pen[k]);", "pen = std::numeric_limits<R>::infinity(); for (int k = 0; k < 2; ++k) if (m.active[k]) pen = std::min(pen, m.pen[k]);"),
+    ("joint positional correction dropped", "V2<R> c = (R(P.joint_beta) / (a.inv_mass + b.inv_mass)) * (xa - xb);", "V2<R> c = R(0) * (xa - xb);"),
+    ("sweeps: collisions before joints", "    for (int q = 0; q < nJ; ++q)\n      if (jrs[q].live) solve_joint(E, E.joints[q], jrs[q]);\n    if (P.batch_size > 0) {", "    if (P.batch_size > 0) {"),
+    ("level order: one past the last predecessor", "      while ((busy >> lv) & 1u) ++lv;\n      if (movable(cps[q].a)) taken[cps[q].a] |= 1u << lv;", "      while ((busy >> lv) != 0u) ++lv;\n      if (movable(cps[q].a)) taken[cps[q].a] |= 1u << lv;"),
+    ("level order: static shapes tie pairs together", "unsigned busy = (movable(cps[q].a) ? taken[cps[q].a] : 0u) | (movable(cps[q].b) ? taken[cps[q].b] : 0u);", "unsigned busy = taken[cps[q].a] | taken[cps[q].b]; taken[cps[q].a] |= 1u << 0; "),
+    ("tournament order: last round first", "      else { x = (r + k) % (m - 1); y = ((r - k) % (m - 1) + (m - 1)) % (m - 1); }", "      else { x = (r + k) % (m - 1); y = ((r - k) % (m - 1) + (m - 1)) % (m - 1); std::swap(x, y); x = (x + 1) % (m - 1); y = (y + 1) % (m - 1); }"),
+    ("batches: impulses applied in reverse point order", "    for (const Pending& p : pend) {", "    std::reverse(pend.begin(), pend.end());\n    for (const Pending& p : pend) {"),
+    ("observation: angular velocity not scaled", "*o++ = Fn<R>::tanh(b.omega / R(10));", "*o++ = Fn<R>::tanh(b.omega);"),
+]
+
+
+# Mistakes that change nothing but the order in which fp32 roundings happen: no closed form or invariant sees
+# them; they are held only by the bit-for-bit comparison of the two implementations (the GPU tests).
+ROUNDING_ORDER_ONLY = {"batches: impulses applied in reverse point order"}
+
+
+def run_one(entry, pytest_args):
+    name, old, new = entry
+    text = open(SRC).read()
+    if text.count(old) != 1:
+        return name, "SKIPPED (text occurs %d times)" % text.count(old), ""
+    with tempfile.TemporaryDirectory(prefix="k2d_mut_") as tmp:
+        src = os.path.join(tmp, "k2d_oracle.cpp")
+        open(src, "w").write(text.replace(old, new))
+        env = dict(os.environ, K2D_ORACLE_SOURCE=src)
+        r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests"), "-x", "-q", "-m", "not gpu",
+                            "-p", "no:cacheprovider"] + pytest_args, cwd=tmp, env=env, capture_output=True, text=True)
+        tail = [l for l in r.stdout.splitlines() if l.startswith(("FAILED", "ERROR"))]
+        if r.returncode == 0:
+            return name, "SURVIVED", ""
+        if "error:" in r.stdout + r.stderr and not tail:
+            return name, "DID NOT COMPILE", (r.stdout + r.stderr)[-400:]
+        return name, "noticed", tail[0] if tail else r.stdout[-200:]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("-j", type=int, default=4)
+    ap.add_argument("-k", default="")
+    args = ap.parse_args()
+    todo = [m for m in MUTANTS if args.k in m[0]]
+    survived = 0
+    with cf.ThreadPoolExecutor(args.j) as ex:
+        for name, verdict, detail in ex.map(lambda m: run_one(m, []), todo):
+            if verdict == "SURVIVED" and name in ROUNDING_ORDER_ONLY:
+                verdict = "survived (rounding order only; held by the bit-identity tests)"
+            else:
+                survived += verdict != "noticed"
+            print("%-58s %s  %s" % (name, verdict, detail.replace(ROOT + "/", "")[:120]), flush=True)
+    print("%d planted mistakes, %d not noticed" % (len(todo), survived))
+    return 1 if survived else 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

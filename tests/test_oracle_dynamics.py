@@ -79,6 +79,40 @@ def test_head_on_circles_restitution(e, mass_ratio):
     assert np.allclose(v[:, 1], 0) and np.allclose(o.state()["omega"], 0)
 
 
+def test_positional_correction_uses_the_deepest_point_of_the_pair():
+    """A.3.7 with a two-point manifold: a tilted box sunk into the floor, nothing moving, no sweeps.  One substep
+    moves the box out along the normal by beta * (deepest penetration - slop), the floor not at all."""
+    sb = SceneBuilder(CAPS)
+    sb.box(5.0, 0.5, (0.0, -0.5), static=True)
+    tilt = 0.05
+    box = sb.box(0.5, 0.3, (0.0, 0.3 * np.cos(tilt) + 0.5 * np.sin(tilt) - 0.06), theta=tilt)
+    p = params(gravity_y=0.0, n_iters=0, warm_start=0, beta=0.2, slop=0.005)
+    o, sc = run(sb, p)
+    o.step(zeros_actions(1, 1, CAPS))
+    N = CAPS[0] + CAPS[1]
+    pi = pair_index(0, box, N)
+    pen = o.get("manifold_pen").reshape(1, -1, 2)[0, pi]
+    act = o.get("pair_active").reshape(1, -1, 2)[0, pi]
+    nrm = o.get("manifold_normal").reshape(1, -1, 2)[0, pi]
+    assert act.all() and pen.max() == pytest.approx(0.06, abs=1e-9) and pen.max() - pen.min() > 0.04
+    assert nrm == pytest.approx([0.0, 1.0], abs=1e-12)
+    moved = o.state()["pos"].reshape(-1, 2)[box] - sc["pos"][0, box]
+    assert moved == pytest.approx(0.2 * (pen.max() - 0.005) * nrm, abs=1e-12)
+    assert np.array_equal(o.state()["pos"].reshape(-1, 2)[0], sc["pos"][0, 0])
+
+
+def test_restitution_of_a_pair_is_the_smaller_of_the_two():
+    """A.3.5: e = min(e_a, e_b).  A bouncy circle meets a dead one head-on: the relative normal velocity becomes
+    -0.2 times what it was, not -0.9 times."""
+    sb = SceneBuilder(CAPS)
+    a = sb.circle(0.5, (-0.6, 0.0), vel=(2.0, 0.0), restitution=0.9, friction=0.0)
+    b = sb.circle(0.5, (0.6, 0.0), vel=(-1.0, 0.0), restitution=0.2, friction=0.0)
+    o, _ = run(sb, params(gravity_y=0.0, alpha=0.0, beta=0.0, n_iters=4))
+    o.step(zeros_actions(12, 1, CAPS))
+    v = o.state()["vel"].reshape(-1, 2)
+    assert v[a, 0] - v[b, 0] == pytest.approx(-0.2 * 3.0, abs=1e-12)
+
+
 def test_slow_approach_has_no_bounce():
     """Below the restitution threshold the collision is inelastic even for e = 1."""
     sb = SceneBuilder(CAPS)
@@ -349,6 +383,32 @@ def test_motor_drives_relative_speed_to_target_and_conserves_angular_momentum():
     jr = 0.05 * np.tanh((0.0 - 0.0 - 3.0 * 0.5) * 1.0) * p["dt"]
     w = o.state()["omega"][0]
     assert w[a] == pytest.approx(-jr / Ia, rel=1e-12) and w[b] == pytest.approx(jr / Ib, rel=1e-12)
+
+
+def test_all_motors_see_the_velocities_from_before_any_motor():
+    """A.8: motors are applied in parallel.  Three shapes in a chain, a motor in either joint, no sweeps (so that
+    nothing but the motors acts): the middle shape receives both impulses, and each is the tanh law of the angular
+    velocities the substep started with -- not of what the other motor left."""
+    caps = (3, 1, 2, 0)
+    sb = SceneBuilder(caps)
+    a = sb.box(0.4, 0.4, (0.0, 0.0), omega=1.0)
+    b = sb.box(0.3, 0.3, (0.0, 0.0), omega=0.25)
+    c = sb.box(0.2, 0.5, (0.0, 0.0), omega=-2.0)
+    sb.joint(a, b, (0.0, 0.0), motor_on=True, speed=3.0, power=0.05)
+    sb.joint(b, c, (0.0, 0.0), motor_on=True, speed=2.0, power=0.08)
+    p = params(gravity_y=0.0, rho=0.7, n_iters=0, warm_start=0, joint_beta=0.0)
+    o, sc = run(sb, p, caps=caps)
+    act = np.array([[[0.5, -0.25]]])
+    o.step(act)
+    ii = sc["inv_inertia"][0]
+    m1 = 0.05 * np.tanh((1.0 - 0.25 - 3.0 * 0.5) * 0.7) * p["dt"]
+    m2 = 0.08 * np.tanh((0.25 + 2.0 - 2.0 * -0.25) * 0.7) * p["dt"]
+    w = o.state()["omega"][0]
+    assert w[a] == pytest.approx(1.0 - ii[a] * m1, rel=1e-13)
+    assert w[b] == pytest.approx(0.25 + ii[b] * m1 - ii[b] * m2, rel=1e-13)
+    assert w[c] == pytest.approx(-2.0 + ii[c] * m2, rel=1e-13)
+    m2_seq = 0.08 * np.tanh((0.25 + ii[b] * m1 + 2.0 - 2.0 * -0.25) * 0.7) * p["dt"]
+    assert abs(m2_seq - m2) > 1e-6 * abs(m2)                 # the other reading would show
 
 
 def test_motor_off_or_fixed_joint_ignores_action():
