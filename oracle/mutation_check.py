@@ -76,6 +76,20 @@ MUTANTS = [
     ("level order: static shapes tie pairs together", "unsigned busy = (movable(cps[q].a) ? taken[cps[q].a] : 0u) | (movable(cps[q].b) ? taken[cps[q].b] : 0u);", "unsigned busy = taken[cps[q].a] | taken[cps[q].b]; taken[cps[q].a] |= 1u << 0; "),
     ("tournament order: last round first", "      else { x = (r + k) % (m - 1); y = ((r - k) % (m - 1) + (m - 1)) % (m - 1); }", "      else { x = (r + k) % (m - 1); y = ((r - k) % (m - 1) + (m - 1)) % (m - 1); std::swap(x, y); x = (x + 1) % (m - 1); y = (y + 1) % (m - 1); }"),
     ("batches: impulses applied in reverse point order", "    for (const Pending& p : pend) {", "    std::reverse(pend.begin(), pend.end());\n    for (const Pending& p : pend) {"),
+    ("batches: solved on the bodies themselves, not on private copies", "Body<R> a = E.bodies[cp.a], bb = E.bodies[cp.b];   // private copies: the batch's starting velocities", "Body<R>& a = E.bodies[cp.a]; Body<R>& bb = E.bodies[cp.b];"),
+    ("batches: consecutive points share a batch", "    for (int s = b; s < n_points; s += n_b) {", "    for (int s = b * B; s < std::min(n_points, (b + 1) * B); ++s) {"),
+    ("substep length ignores the number of substeps", "const R h = R(P.dt) / R(P.n_substeps);", "const R h = R(P.dt);"),
+    ("joint accumulators kept without warm starting", "if (!P.warm_start) { jt.acc = {0, 0}; jt.acc_ang = 0; }", ""),
+    ("joint warm start with the wrong sign on b", "      apply_impulse(b, V2<R>{-jt.acc.x, -jt.acc.y}, jrs[q].rb);\n    }\n  }", "      apply_impulse(b, V2<R>{jt.acc.x, jt.acc.y}, jrs[q].rb);\n    }\n  }"),
+    ("thruster clip clamps to [-1, 1]", "if (P.clip_thruster_01) A = std::min(std::max(A, R(0)), R(1));", "if (P.clip_thruster_01) A = std::min(std::max(A, R(-1)), R(1));"),
+    ("pair count counts pairs, not points", "out[(long)e * NP + p] = envs[e].manifolds[p].active[0] + envs[e].manifolds[p].active[1];", "out[(long)e * NP + p] = envs[e].manifolds[p].active[0] || envs[e].manifolds[p].active[1];"),
+    ("adjacency one-sided", "if (m.active[0] || m.active[1]) { adj[i] |= 1u << j; adj[j] |= 1u << i; }", "if (m.active[0] || m.active[1]) { adj[i] |= 1u << j; }"),
+    ("collision active at zero penetration", "m.active[k] = m.valid[k] && m.pen[k] > R(0);", "m.active[k] = m.valid[k] && m.pen[k] >= R(-1e-3);"),
+    ("static-static pairs eligible", "m.eligible = a.active && b.active && !joined[i * N + j] && (a.inv_mass + b.inv_mass) > R(0);", "m.eligible = a.active && b.active && !joined[i * N + j];"),
+    ("observation: sin and cos of the rotation swapped", "        { V2<R> u = unit(b.theta); *o++ = u.y; *o++ = u.x; }", "        { V2<R> u = unit(b.theta); *o++ = u.x; *o++ = u.y; }"),
+    ("observation: joint rotation b - a", "R rel = E.bodies[ja].theta - E.bodies[jb].theta;\n        *o++ = j.active;", "R rel = E.bodies[jb].theta - E.bodies[ja].theta;\n        *o++ = j.active;"),
+    ("observation: thruster power and position swapped", "*o++ = t.active; *o++ = t.pos.x; *o++ = t.pos.y; *o++ = t.power;", "*o++ = t.active; *o++ = t.power; *o++ = t.pos.x; *o++ = t.pos.y;"),
+    ("observation: restitution before friction", "*o++ = b.friction; *o++ = b.restitution;", "*o++ = b.restitution; *o++ = b.friction;"),
     ("observation: angular velocity not scaled", "*o++ = Fn<R>::tanh(b.omega / R(10));", "*o++ = Fn<R>::tanh(b.omega);"),
 ]
 

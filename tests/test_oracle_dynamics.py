@@ -484,6 +484,41 @@ def test_warm_start_bookkeeping():
     assert st["lambda_n"][0, 2 * q] == 0 and st["lambda_t"][0, 2 * q] == 0 and st["prev_active"][0, 2 * q] == 0
 
 
+def test_a_collision_is_active_only_with_positive_penetration_and_adjacency_is_symmetric():
+    """Table 2: a manifold point is an active collision iff its penetration is positive.  Two circles half a
+    millimetre apart do not collide (no count, no adjacency, no impulse); half a millimetre into each other they
+    do, and each shape's adjacency word names the other."""
+    N = CAPS[0] + CAPS[1]
+    for gap, touching in ((5e-4, False), (-5e-4, True)):
+        sb = SceneBuilder(CAPS)
+        a = sb.circle(0.5, (0.0, 0.0), vel=(0.5, 0.0))
+        b = sb.circle(0.5, (1.0 + gap, 0.0), vel=(0.5, 0.0))
+        o, _ = run(sb, params(gravity_y=0.0, alpha=0.0, beta=0.0, slop=0.0))
+        o.step(zeros_actions(1, 1, CAPS))
+        count = o.get("pair_count")[0, pair_index(a, b, N)]
+        adj = o.get("shape_adj")[0].astype(np.int64)
+        assert count == (1 if touching else 0)
+        assert ((adj[a] >> b) & 1) == int(touching) and ((adj[b] >> a) & 1) == int(touching)
+        assert [int(x) for x in adj if x] == ([1 << b, 1 << a] if touching else [])
+        assert np.array_equal(o.state()["vel"].reshape(-1, 2)[[a, b]], [[0.5, 0.0], [0.5, 0.0]])
+
+
+def test_joint_accumulators_without_warm_starting_hold_one_substep_only():
+    """A.7 off: nothing is carried over, so after any number of steps the accumulated impulse of a joint that holds
+    a hanging weight is the impulse of one substep, m g h -- not the sum over the substeps so far."""
+    caps = (1, 1, 1, 0)
+    sb = SceneBuilder(caps)
+    top = sb.box(0.5, 0.1, (0.0, 2.0), static=True)
+    bob = sb.circle(0.2, (0.0, 1.0))
+    sb.joint(top, bob, (0.0, 2.0))
+    p = params(n_substeps=2, n_iters=10, warm_start=0)
+    o, sc = run(sb, p, caps=caps)
+    o.step(zeros_actions(30, 1, caps))
+    m = 1 / sc["inv_mass"][0, bob]
+    acc = o.state()["joint_acc"][0, :2]
+    assert abs(acc[1]) == pytest.approx(m * 9.81 * p["dt"] / 2, rel=0.05) and abs(acc[0]) < 1e-6
+
+
 def test_warm_start_off_and_on_reach_the_same_rest_but_on_is_faster():
     res = {}
     for ws in (0, 1):
