@@ -99,6 +99,64 @@ MUTANTS = [
 ROUNDING_ORDER_ONLY = {"batches: impulses applied in reverse point order"}
 
 
+# The same for the numpy statement of the environment layer (oracle/k2d_env.py: reward and termination, entity
+# observation and masks, multi-discrete actions, health).
+ENV_SRC = os.path.join(HERE, "k2d_env.py")
+ENV_MUTANTS = [
+    ("reward: red counts as the goal", "sparse = f(1) if goal else (f(-1) if bad else f(0))", "sparse = f(1) if (goal or bad) else f(0)"),
+    ("reward: red wins over blue", "sparse = f(1) if goal else (f(-1) if bad else f(0))", "sparse = f(-1) if bad else (f(1) if goal else f(0))"),
+    ("reward: dense term with the wrong sign", "dense = f(f(kappa) * f(f(d_prev[e]) - d_new[e]))", "dense = f(f(kappa) * f(d_new[e] - f(d_prev[e])))"),
+    ("reward: dense term on the first step", "if d_prev[e] >= 0 and best is not None:", "if best is not None:"),
+    ("reward: largest distance over the pairs", "best = d if best is None or d < best else best", "best = d if best is None or d > best else best"),
+    ("reward: inactive shapes count", "if j == i or not active[e, j]:", "if j == i:"),
+    ("reward: any shape may reach the goal", "if not active[e, i] or role[e, i] != green:", "if not active[e, i]:"),
+    ("reward: episode does not end on red", "done[e] = 1 if (goal or bad) else 0", "done[e] = 1 if goal else 0"),
+    ("actions: motor directions swapped", "np.where(m == 1, 1.0, np.where(m == 2, -1.0, 0.0))", "np.where(m == 1, -1.0, np.where(m == 2, 1.0, 0.0))"),
+    ("actions: thruster on at 2", "np.where(d[..., J:] == 1, 1.0, 0.0)", "np.where(d[..., J:] == 2, 1.0, 0.0)"),
+    ("entities: role one-hot shifted", "s[8 + role] = 1.0", "s[8 + (role + 1) % N_ROLES] = 1.0"),
+    ("entities: type one-hot swapped", "s[16 if i >= P else 17] = 1.0", "s[17 if i >= P else 16] = 1.0"),
+    ("entities: triangle and rectangle swapped", "s[27 if int(f[20]) == 3 else 28] = 1.0", "s[28 if int(f[20]) == 3 else 27] = 1.0"),
+    ("entities: reversed joint keeps its anchors", "g[2:4], g[4:6] = f[4:6], f[2:4]", "g[2:4], g[4:6] = f[2:4], f[4:6]"),
+    ("entities: reversed joint keeps its rotation", "g[9] = -f[9]", "g[9] = f[9]"),
+    ("entities: reversed joint's shapes not swapped", "jidx[e, 2 * q + 1] = (b, a)", "jidx[e, 2 * q + 1] = (a, b)"),
+    ("masks: joints on inactive shapes count", "if f[0] != 0 and act[a] and act[b] and a != b:", "if f[0] != 0 and a != b:"),
+    ("masks: joint mask one-sided", "                direct[b] |= 1 << a\n", "                pass\n"),
+    ("masks: no transitive closure", "                    reach[i] |= reach[k]", "                    reach[i] |= 0"),
+    ("masks: collision mask is the joint mask", "masks[e, 3, i] = int(shape_adj[e, i])", "masks[e, 3, i] = direct[i]"),
+    ("masks: inactive shapes attend", "masks[e, 0, i] = full if act[i] else 0", "masks[e, 0, i] = full"),
+    ("health: inactive shapes count", "bad = ((~finite) & (np.asarray(active) != 0)).any(-1)", "bad = (~finite).any(-1)"),
+    ("health: infinities pass", "np.isfinite(pos).all(-1) & np.isfinite(theta)", "(~np.isnan(pos)).all(-1) & np.isfinite(theta)"),
+]
+
+_ENV_RUNNER = """
+import sys, importlib.util
+sys.path.insert(0, {root!r}); sys.path.insert(0, {tests!r})
+import oracle, pytest
+spec = importlib.util.spec_from_file_location("oracle.k2d_env", {mut!r})
+m = importlib.util.module_from_spec(spec)
+sys.modules["oracle.k2d_env"] = m
+spec.loader.exec_module(m)
+oracle.k2d_env = m
+sys.exit(pytest.main([{tests!r}, "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider"]))
+"""
+
+
+def run_env_one(entry):
+    name, old, new = entry
+    text = open(ENV_SRC).read()
+    if text.count(old) != 1:
+        return name, "SKIPPED (text occurs %d times)" % text.count(old), ""
+    with tempfile.TemporaryDirectory(prefix="k2d_mut_") as tmp:
+        mut = os.path.join(tmp, "k2d_env.py")
+        open(mut, "w").write(text.replace(old, new))
+        code = _ENV_RUNNER.format(root=ROOT, tests=os.path.join(ROOT, "tests"), mut=mut)
+        r = subprocess.run([sys.executable, "-c", code], cwd=tmp, capture_output=True, text=True)
+        tail = [l for l in r.stdout.splitlines() if l.startswith(("FAILED", "ERROR"))]
+        if r.returncode == 0:
+            return name, "SURVIVED", ""
+        return name, "noticed", tail[0] if tail else (r.stdout + r.stderr)[-200:]
+
+
 def run_one(entry, pytest_args):
     name, old, new = entry
     text = open(SRC).read()
@@ -124,15 +182,17 @@ def main():
     ap.add_argument("-k", default="")
     args = ap.parse_args()
     todo = [m for m in MUTANTS if args.k in m[0]]
+    todo_env = [m for m in ENV_MUTANTS if args.k in m[0]]
     survived = 0
     with cf.ThreadPoolExecutor(args.j) as ex:
-        for name, verdict, detail in ex.map(lambda m: run_one(m, []), todo):
+        results = list(ex.map(lambda m: run_one(m, []), todo)) + list(ex.map(run_env_one, todo_env))
+        for name, verdict, detail in results:
             if verdict == "SURVIVED" and name in ROUNDING_ORDER_ONLY:
                 verdict = "survived (rounding order only; held by the bit-identity tests)"
             else:
                 survived += verdict != "noticed"
             print("%-58s %s  %s" % (name, verdict, detail.replace(ROOT + "/", "")[:120]), flush=True)
-    print("%d planted mistakes, %d not noticed" % (len(todo), survived))
+    print("%d planted mistakes, %d not noticed" % (len(todo) + len(todo_env), survived))
     return 1 if survived else 0
 
 

@@ -90,39 +90,44 @@ def test_distance_is_the_smallest_over_pairs_and_zero_without_a_pair():
 
 # ------------------------------------------------------------------ entity observation, action decoding
 def test_entity_observation_on_a_hand_built_chain():
-    """Three shapes in a chain a - b - c (two joints) and a loose fourth: one-hots, the two views of a joint,
-    and the masks (direct neighbours vs. everything reachable over joints)."""
-    caps = (2, 2, 2, 1)
+    """Three shapes in a chain a - b - c (two joints), a loose fourth and an inactive fifth with a joint of its
+    own: one-hots, the two views of a joint, and the masks (direct neighbours vs. everything reachable over
+    joints; inactive shapes neither attend nor are attended to)."""
+    caps = (2, 3, 3, 1)
     sb = SceneBuilder(caps)
-    a = sb.box(0.3, 0.2, (0.0, 1.0), role=1)
+    a = sb.box(0.3, 0.2, (0.0, 1.0), role=1, theta=0.4)
     tri = sb.polygon(np.array([[-0.3, -0.1], [0.3, -0.1], [0.0, 0.2]]), (0.5, 1.0), role=3)   # centred on its centroid
     c = sb.circle(0.15, (1.0, 1.0), role=2)
     loose = sb.circle(0.1, (3.0, 3.0))
+    ghost = sb.circle(0.1, (1.2, 1.0))
     sb.joint(a, tri, (0.25, 1.0), motor_on=True, speed=2.0, power=0.5)
     sb.joint(tri, c, (0.75, 1.0), fixed=True)
+    sb.joint(c, ghost, (1.1, 1.0))
+    sb.sc["active"][0, ghost] = 0
     sb.thruster(c, (0.05, 0.0), angle=0.3, power=1.5)
     sc = sb.scene(f32=True)
     o = Oracle(caps, 1, params(gravity_y=0.0), "f32")
     o.load_scene(sc)
     ent = k2d_env.entities(o.obs(), sc, o.get("shape_adj"), caps)
     S = ent["shapes"][0]
-    assert S.shape == (4, 30)
+    assert S.shape == (5, 30)
     assert list(S[a, 8:12]) == [0, 1, 0, 0] and list(S[tri, 8:12]) == [0, 0, 0, 1] and list(S[c, 8:12]) == [0, 0, 1, 0]
     assert list(S[a, 16:18]) == [0, 1] and list(S[c, 16:18]) == [1, 0]           # circle, polygon
     assert list(S[a, 27:29]) == [0, 1] and list(S[tri, 27:29]) == [1, 0]         # triangle, rectangle
     assert S[c, 18] == np.float32(0.15) and S[a, 18] == 0 and (S[c, 19:29] == 0).all()
-    assert S[a, 0] == 0.0 and S[a, 1] == 1.0 and (S[:, 29] == 1).all()
+    assert S[a, 0] == 0.0 and S[a, 1] == 1.0 and list(S[:, 29]) == [1, 1, 1, 1, 0]
     J = ent["joints"][0]
     assert list(ent["joint_idx"][0, 0]) == [a, tri] and list(ent["joint_idx"][0, 1]) == [tri, a]
     assert np.array_equal(J[0, 2:4], J[1, 4:6]) and np.array_equal(J[0, 4:6], J[1, 2:4])
-    assert J[0, 9] == -J[1, 9] and J[0, 10] == J[1, 10] and J[0, 8] == 1 and J[2, 1] == 1
+    assert J[0, 9] == pytest.approx(np.sin(0.4), abs=2e-7) and J[0, 10] == pytest.approx(np.cos(0.4), abs=2e-7)
+    assert J[1, 9] == -J[0, 9] and J[1, 10] == J[0, 10] and J[0, 8] == 1 and J[2, 1] == 1
     assert list(ent["thruster_idx"][0]) == [c] and ent["thrusters"][0, 0, 3] == np.float32(1.5)
     M = ent["masks"][0]
     bit = lambda *idx: sum(1 << i for i in idx)
-    assert list(M[0]) == [bit(a, tri, c, loose)] * 4
-    assert list(M[1]) == [bit(a, tri), bit(a, tri, c), bit(tri, c), bit(loose)]
-    assert list(M[2]) == [bit(a, tri, c)] * 3 + [bit(loose)]
-    assert list(M[3]) == [0, 0, 0, 0]
+    assert list(M[0]) == [bit(a, tri, c, loose)] * 4 + [0]
+    assert list(M[1]) == [bit(a, tri), bit(a, tri, c), bit(tri, c), bit(loose), 0]
+    assert list(M[2]) == [bit(a, tri, c)] * 3 + [bit(loose), 0]
+    assert list(M[3]) == [0, 0, 0, 0, 0]
 
 
 def test_multi_discrete_actions():
@@ -155,7 +160,7 @@ def test_observation_widths_match_the_papers_tables():
 
 # ------------------------------------------------------------------ health of the batch
 def test_health_flags_non_finite_active_shapes_only():
-    n, N = 6, 4
+    n, N = 7, 4
     pos, vel = np.zeros((n, N, 2)), np.ones((n, N, 2))
     theta, omega = np.zeros((n, N)), np.zeros((n, N))
     active = np.ones((n, N), dtype=np.int64)
@@ -165,8 +170,9 @@ def test_health_flags_non_finite_active_shapes_only():
     omega[3, 3] = np.nan            # inactive shape: ignored
     theta[4, 1] = np.inf            # active: flagged
     vel[5, 0] = 3.0e38              # huge but finite: fine
+    pos[6, 1, 0] = np.inf           # an infinite position is as bad as a NaN
     bad, count = k2d_env.health(pos, theta, vel, omega, active)
-    assert bad.tolist() == [0, 1, 1, 0, 1, 0] and count == 3
+    assert bad.tolist() == [0, 1, 1, 0, 1, 0, 1] and count == 4
 
 
 # ------------------------------------------------------------------ values of the flat observation
