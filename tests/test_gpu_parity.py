@@ -259,8 +259,9 @@ def test_heterogeneous_batch_with_resets():
         assert np.array_equal(gs[k], os_[k]), k
 
 
-@pytest.mark.parametrize("cfg,n,steps", [(4, 195, 24), (1, 131, 30), (0, 67, 20)])
-def test_resets_inside_one_launch(cfg, n, steps):
+@pytest.mark.parametrize("cfg,n,steps,sweep_order", [(4, 195, 24, 0), (1, 131, 30, 0), (0, 67, 20, 0), (4, 195, 24, 1),
+                                                     (3, 131, 20, 1)])
+def test_resets_inside_one_launch(cfg, n, steps, sweep_order):
     """k2d_step_reset: the protocol of the heterogeneous workload (a seeded 5 % of the environments restart
     from new scenes after every step) in ONE launch, against the oracle stepped and reloaded from the host,
     and against the GPU path that alternates k2d_step(1) and k2d_reset."""
@@ -268,6 +269,7 @@ def test_resets_inside_one_launch(cfg, n, steps):
     import paper_2410_23208_amd as k2d
     from oracle.k2d_oracle import Oracle
     caps, prm, sc = scenegen.make_scene(cfg, n_envs=n)
+    prm = dict(prm, sweep_order=sweep_order)
     act = scenegen.make_actions(cfg, steps, n)
     o = Oracle(caps, n, prm, "f32")
     o.load_scene(sc)
