@@ -383,6 +383,21 @@ def _hand_scene_parity(sb, prm, steps, n_envs=1):
     return gs, os_
 
 
+@pytest.mark.parametrize("cfg,lanes", [(2, 0), (0, 8), (1, 0)])
+def test_ordered_launch_of_small_ragged_batches(cfg, lanes):
+    """Launches long enough to be ordered (8 steps and more), with so few environments that the classes of the
+    ordering (environments sharing an action line, one class per XCD) do not fill their wavefronts evenly: every
+    environment must still be stepped exactly once."""
+    for n in (2, 3, 5, 9, 17, 31, 33, 47, 65):
+        caps, prm, sc = scenegen.make_scene(cfg, n_envs=n)
+        act = scenegen.make_actions(cfg, 10, n)
+        o = parity.run_oracle(caps, prm, sc, act)
+        b = parity.run_gpu(caps, prm, sc, act, lanes=lanes)
+        gs, os_ = b.state_dict(), o.state()
+        for k in parity.FLOAT_KEYS + parity.INT_KEYS:
+            assert np.array_equal(gs[k], os_[k]), (n, k)
+
+
 def test_single_environment_and_empty_scene():
     caps = scenegen.CAPS["S"]
     sb = SceneBuilder(caps)                      # nothing active at all
